@@ -1,0 +1,148 @@
+"""ctypes binding of ``libspdy_dp.so`` (declared in ``include/spdy_dp.h``).
+
+Marshalling only: every step of Alg. 1 runs in the HIP kernels.  PyTorch supplies device memory
+and the stream.  There is no CPU fallback: a missing library or a non-GPU tensor is an error.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libspdy_dp.so")
+_lib = None
+
+OK = 0
+ERR_NULL, ERR_DIM, ERR_LEVELS, ERR_WORKSPACE, ERR_OVERFLOW, ERR_LAUNCH = -1, -2, -3, -4, -5, -9
+
+EXPORTS = ("spdy_dp_workspace_bytes", "spdy_dp_solve_batched", "spdy_dp_fill",
+           "spdy_dp_backtrace", "spdy_dp_workspace_layout", "spdy_dp_strerror")
+
+
+class SpdyDpError(RuntimeError):
+    def __init__(self, status: int):
+        self.status = status
+        super().__init__(f"spdy_dp status {status}: {spdy_dp_strerror(status)}")
+
+
+def lib() -> ctypes.CDLL:
+    """Load the HIP library built in-tree; fails loudly if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it first (python -m paper_2201_13096_amd.build); "
+                "there is no fallback path")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
+        L.spdy_dp_workspace_bytes.restype = sz
+        L.spdy_dp_workspace_bytes.argtypes = [i, i, i, i]
+        L.spdy_dp_solve_batched.restype = i
+        L.spdy_dp_solve_batched.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, sz, vp]
+        L.spdy_dp_fill.restype = i
+        L.spdy_dp_fill.argtypes = [vp, vp, i, i, i, i, vp, vp, sz, vp]
+        L.spdy_dp_backtrace.restype = i
+        L.spdy_dp_backtrace.argtypes = [vp, i, i, i, i, vp, vp, sz, vp]
+        L.spdy_dp_workspace_layout.restype = i
+        L.spdy_dp_workspace_layout.argtypes = [i, i, i, i, ctypes.POINTER(sz), ctypes.POINTER(sz),
+                                               ctypes.POINTER(sz)]
+        L.spdy_dp_strerror.restype = ctypes.c_char_p
+        L.spdy_dp_strerror.argtypes = [i]
+        _lib = L
+    return _lib
+
+
+def spdy_dp_strerror(status: int) -> str:
+    return lib().spdy_dp_strerror(int(status)).decode()
+
+
+def spdy_dp_workspace_bytes(K: int, L: int, S: int, B: int) -> int:
+    return int(lib().spdy_dp_workspace_bytes(K, L, S, B))
+
+
+def spdy_dp_workspace_layout(K: int, L: int, S: int, B: int):
+    """(choice_offset, choice_pitch, tstar_offset) in bytes."""
+    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
+    st = lib().spdy_dp_workspace_layout(K, L, S, B, ctypes.byref(a), ctypes.byref(b),
+                                        ctypes.byref(c))
+    if st != OK:
+        raise SpdyDpError(st)
+    return a.value, b.value, c.value
+
+
+def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise TypeError(f"{name} must be a tensor on the GPU")
+    if t.dtype != dtype or not t.is_contiguous():
+        raise TypeError(f"{name} must be contiguous {dtype}")
+    return t
+
+
+def _shapes(tau: torch.Tensor, err: torch.Tensor):
+    if tau.dim() != 2 or err.dim() != 3 or tuple(err.shape[1:]) != tuple(tau.shape):
+        raise ValueError("tau must be [L, S] and err [K, L, S]")
+    K, L, S = err.shape
+    return int(K), int(L), int(S)
+
+
+def _stream(stream) -> int:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return int(stream.cuda_stream)
+
+
+def alloc_workspace(K: int, L: int, S: int, B: int, device=None) -> torch.Tensor:
+    n = spdy_dp_workspace_bytes(K, L, S, B)
+    if n == 0:
+        raise SpdyDpError(lib().spdy_dp_workspace_layout(
+            K, L, S, B, ctypes.byref(ctypes.c_size_t()), ctypes.byref(ctypes.c_size_t()),
+            ctypes.byref(ctypes.c_size_t())))
+    return torch.empty(n, dtype=torch.uint8, device=device or "cuda")
+
+
+def spdy_dp_solve_batched(tau, err, B: int, profile=None, cost=None, workspace=None, stream=None):
+    """Whole of Alg. 1 for K candidates.  Returns ``(profile int16[K,L], cost fp32[K])`` (device
+    tensors, valid after the stream is synchronised)."""
+    tau = _dev(tau, torch.int32, "tau")
+    err = _dev(err, torch.float32, "err")
+    K, L, S = _shapes(tau, err)
+    if profile is None:
+        profile = torch.empty((K, L), dtype=torch.int16, device=err.device)
+    if cost is None:
+        cost = torch.empty((K,), dtype=torch.float32, device=err.device)
+    if workspace is None:
+        workspace = alloc_workspace(K, L, S, B, err.device)
+    _dev(profile, torch.int16, "profile")
+    _dev(cost, torch.float32, "cost")
+    _dev(workspace, torch.uint8, "workspace")
+    st = lib().spdy_dp_solve_batched(tau.data_ptr(), err.data_ptr(), K, L, S, int(B),
+                                     profile.data_ptr(), cost.data_ptr(), workspace.data_ptr(),
+                                     workspace.numel(), _stream(stream))
+    if st != OK:
+        raise SpdyDpError(st)
+    return profile, cost
+
+
+def spdy_dp_fill(tau, err, B: int, cost, workspace, stream=None) -> None:
+    tau = _dev(tau, torch.int32, "tau")
+    err = _dev(err, torch.float32, "err")
+    K, L, S = _shapes(tau, err)
+    _dev(cost, torch.float32, "cost")
+    _dev(workspace, torch.uint8, "workspace")
+    st = lib().spdy_dp_fill(tau.data_ptr(), err.data_ptr(), K, L, S, int(B), cost.data_ptr(),
+                            workspace.data_ptr(), workspace.numel(), _stream(stream))
+    if st != OK:
+        raise SpdyDpError(st)
+
+
+def spdy_dp_backtrace(tau, K: int, B: int, profile, workspace, stream=None) -> None:
+    tau = _dev(tau, torch.int32, "tau")
+    L, S = (int(x) for x in tau.shape)
+    _dev(profile, torch.int16, "profile")
+    _dev(workspace, torch.uint8, "workspace")
+    st = lib().spdy_dp_backtrace(tau.data_ptr(), int(K), L, S, int(B), profile.data_ptr(),
+                                 workspace.data_ptr(), workspace.numel(), _stream(stream))
+    if st != OK:
+        raise SpdyDpError(st)

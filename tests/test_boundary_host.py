@@ -1,0 +1,101 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every function the
+header declares, sizes its workspace as documented and rejects bad arguments before touching
+the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "spdy_dp.h")
+
+
+@pytest.fixture(scope="module")
+def binding():
+    from paper_2201_13096_amd import binding as b
+    if not os.path.exists(b.LIB_PATH):
+        from paper_2201_13096_amd import build
+        build.build_library()
+    return b
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(spdy_dp_\w+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function(binding):
+    names = declared_functions()
+    assert len(names) >= 6
+    lib = ctypes.CDLL(binding.LIB_PATH)
+    for n in names:
+        assert hasattr(lib, n), n
+    assert sorted(binding.EXPORTS) == names
+
+
+def test_status_codes_match_header(binding):
+    text = open(HEADER).read()
+    codes = dict(re.findall(r"#define\s+SPDY_DP_(\w+)\s+\(?(-?\d+)\)?", text))
+    assert int(codes["OK"]) == binding.OK
+    assert int(codes["ERR_NULL"]) == binding.ERR_NULL
+    assert int(codes["ERR_DIM"]) == binding.ERR_DIM
+    assert int(codes["ERR_LEVELS"]) == binding.ERR_LEVELS
+    assert int(codes["ERR_WORKSPACE"]) == binding.ERR_WORKSPACE
+    assert int(codes["ERR_OVERFLOW"]) == binding.ERR_OVERFLOW
+    assert int(codes["ERR_LAUNCH"]) == binding.ERR_LAUNCH
+    for v in codes.values():
+        assert binding.spdy_dp_strerror(int(v)) != "unknown status"
+    assert binding.spdy_dp_strerror(-1234) == "unknown status"
+
+
+def test_workspace_size(binding):
+    # one byte per (k, l, t) with rows padded to 64 buckets, plus t* per candidate
+    K, L, S, B = 1024, 54, 40, 10000
+    row = (B + 1 + 63) // 64 * 64
+    n = binding.spdy_dp_workspace_bytes(K, L, S, B)
+    assert K * L * row + 4 * K <= n <= K * L * row + 4 * K + 1024
+    off, pitch, toff = binding.spdy_dp_workspace_layout(K, L, S, B)
+    assert off == 0 and pitch == row and toff >= K * L * row and toff % 256 == 0
+    # rows that do not fit LDS add two fp32 rows per candidate
+    K, L, S, B = 256, 200, 64, 65536
+    row = (B + 1 + 63) // 64 * 64
+    n = binding.spdy_dp_workspace_bytes(K, L, S, B)
+    assert n >= K * L * row + 2 * K * row * 4
+    # invalid sizes -> 0
+    assert binding.spdy_dp_workspace_bytes(0, 1, 1, 1) == 0
+    assert binding.spdy_dp_workspace_bytes(1, 1, 1, -1) == 0
+    assert binding.spdy_dp_workspace_bytes(1, 1, 256, 1) == 0
+    assert binding.spdy_dp_workspace_bytes(1, 1, 255, 1) > 0
+    assert binding.spdy_dp_workspace_bytes(2 ** 31 - 1, 2 ** 31 - 1, 255, 2 ** 31 - 2000) == 0
+
+
+def test_argument_errors_are_reported_before_any_launch(binding):
+    lib = binding.lib()
+    fake = 0x1000  # never dereferenced: every call below must fail validation first
+    solve = lib.spdy_dp_solve_batched
+    assert solve(None, fake, 1, 1, 1, 1, fake, fake, fake, 1 << 20, None) == binding.ERR_NULL
+    assert solve(fake, None, 1, 1, 1, 1, fake, fake, fake, 1 << 20, None) == binding.ERR_NULL
+    assert solve(fake, fake, 1, 1, 1, 1, None, fake, fake, 1 << 20, None) == binding.ERR_NULL
+    assert solve(fake, fake, 1, 1, 1, 1, fake, None, fake, 1 << 20, None) == binding.ERR_NULL
+    assert solve(fake, fake, 1, 1, 1, 1, fake, fake, None, 1 << 20, None) == binding.ERR_NULL
+    assert solve(fake, fake, 0, 1, 1, 1, fake, fake, fake, 1 << 20, None) == binding.ERR_DIM
+    assert solve(fake, fake, 1, 0, 1, 1, fake, fake, fake, 1 << 20, None) == binding.ERR_DIM
+    assert solve(fake, fake, 1, 1, 0, 1, fake, fake, fake, 1 << 20, None) == binding.ERR_DIM
+    assert solve(fake, fake, 1, 1, 1, -1, fake, fake, fake, 1 << 20, None) == binding.ERR_DIM
+    assert solve(fake, fake, 1, 1, 256, 1, fake, fake, fake, 1 << 20, None) == binding.ERR_LEVELS
+    assert solve(fake, fake, 1, 1, 1, 1, fake, fake, fake, 8, None) == binding.ERR_WORKSPACE
+    assert solve(fake, fake, 2 ** 31 - 1, 2 ** 31 - 1, 2, 2 ** 31 - 2000, fake, fake, fake,
+                 1 << 20, None) == binding.ERR_OVERFLOW
+    assert lib.spdy_dp_fill(fake, fake, 1, 1, 1, 1, None, fake, 1 << 20, None) == binding.ERR_NULL
+    assert lib.spdy_dp_backtrace(fake, 1, 1, 1, 1, None, fake, 1 << 20, None) == binding.ERR_NULL
+    assert lib.spdy_dp_backtrace(fake, 1, 1, 1, 1, fake, fake, 8, None) == binding.ERR_WORKSPACE
+
+
+def test_binding_refuses_cpu_tensors(binding):
+    import torch
+    tau = torch.zeros((2, 2), dtype=torch.int32)
+    err = torch.zeros((1, 2, 2), dtype=torch.float32)
+    with pytest.raises(TypeError):
+        binding.spdy_dp_solve_batched(tau, err, 4)

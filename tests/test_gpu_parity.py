@@ -1,0 +1,171 @@
+"""GPU parity: the HIP path against the CPU oracle, bit for bit (profiles, fp32 costs, and the
+per-cell level record wherever the oracle's D is finite), through the C-ABI binding."""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+import workloads
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+CPU_THREADS = 16
+
+
+@pytest.fixture(scope="module")
+def dp():
+    assert torch.cuda.is_available(), "these tests need the GPU"
+    import paper_2201_13096_amd as m
+    m.binding.lib()  # fails loudly if the HIP library was not built
+    return m
+
+
+def gpu_solve(dp, tau, err, B, stream=None):
+    dev = torch.device("cuda:0")
+    tau_d = torch.from_numpy(tau).to(dev)
+    err_d = torch.from_numpy(err).to(dev)
+    K, L, S = err.shape
+    ws = dp.alloc_workspace(K, L, S, B, dev)
+    ws.fill_(0xAB)   # stale contents must not matter
+    profile = torch.full((K, L), -7, dtype=torch.int16, device=dev)
+    cost = torch.full((K,), -7.0, dtype=torch.float32, device=dev)
+    dp.spdy_dp_solve_batched(tau_d, err_d, B, profile, cost, ws, stream=stream)
+    torch.cuda.synchronize()
+    return profile.cpu().numpy(), cost.cpu().numpy(), ws
+
+
+def assert_same(p_gpu, c_gpu, p_ref, c_ref, what):
+    bad_c = np.flatnonzero(c_gpu.view(np.uint32) != c_ref.view(np.uint32))
+    assert bad_c.size == 0, f"{what}: cost bits differ at candidates {bad_c[:8]}: " \
+                            f"{c_gpu[bad_c[:8]]} vs {c_ref[bad_c[:8]]}"
+    bad_p = np.argwhere(p_gpu != p_ref)
+    assert bad_p.size == 0, f"{what}: profiles differ at (k, l) {bad_p[:8].tolist()}"
+
+
+def check_tables(dp, tau, err_k, B, ws, k, K):
+    """Level record and t* of candidate k against the oracle's P where its D is finite."""
+    L, S = tau.shape
+    D, P, prof, cost = oracle.tables_ref(tau, err_k, B)
+    off, pitch, toff = dp.spdy_dp_workspace_layout(K, L, S, B)
+    wsb = ws.cpu().numpy()
+    rec = wsb[off + k * L * pitch: off + (k + 1) * L * pitch].reshape(L, pitch)[:, :B + 1]
+    finite = np.isfinite(D)
+    assert (rec[finite] == P[finite].astype(np.uint8)).all()
+    tstar = wsb[toff:toff + 4 * K].view(np.int32)[k]
+    if np.isfinite(cost):
+        assert tstar == int(np.argmin(D[L - 1]))
+    else:
+        assert tstar == -1
+
+
+# --------------------------------------------------------------------------- the five configs
+@pytest.mark.parametrize("name", ["tiny", "rn50_k1", "rn50_k1024", "bert_k4096", "stress_k256"])
+def test_config_bit_exact(dp, name):
+    cfg = workloads.CONFIGS[name]
+    print(f"[parity] config {name}: K={cfg.K} L={cfg.L} S={cfg.S} B={cfg.B}", flush=True)
+    tau, err, B = workloads.generate(cfg)
+    p_gpu, c_gpu, ws = gpu_solve(dp, tau, err, B)
+    print(f"[parity] {name}: gpu done, running oracle on {CPU_THREADS} threads", flush=True)
+    p_ref, c_ref = oracle.solve_ref(tau, err, B, threads=CPU_THREADS)
+    assert_same(p_gpu, c_gpu, p_ref, c_ref, name)
+    assert np.isfinite(c_ref).all()
+    # properties that hold at any size: budget met; cost is the layer-order fp32 sum
+    t = np.take_along_axis(np.broadcast_to(tau, err.shape), p_gpu[:, :, None].astype(np.int64),
+                           axis=2)[:, :, 0].sum(axis=1)
+    assert (t <= B).all()
+    e = np.take_along_axis(err, p_gpu[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    acc = e[:, 0].copy()
+    for l in range(1, cfg.L):
+        acc = (acc + e[:, l]).astype(np.float32)
+    assert (acc.view(np.uint32) == c_gpu.view(np.uint32)).all()
+    if cfg.K * cfg.L * (cfg.B + 1) < 2e9:
+        for k in sorted({0, cfg.K // 2, cfg.K - 1}):
+            check_tables(dp, tau, err[k], B, ws, k, cfg.K)
+
+
+# --------------------------------------------------------------------------- shapes and edges
+EDGE_SHAPES = [
+    # K, L, S, B  (B + 1 deliberately not a multiple of 64 in most; several chunks per wave)
+    (3, 1, 1, 0), (2, 1, 5, 7), (4, 5, 1, 100), (5, 6, 7, 63), (5, 6, 7, 64), (3, 9, 12, 1000),
+    (7, 12, 33, 2500), (2, 4, 255, 700), (3, 17, 40, 10000), (2, 20, 16, 16384),
+    (2, 7, 9, 20478), (2, 6, 10, 20479),             # largest rows that still fit LDS
+    (3, 6, 10, 20480), (2, 5, 12, 33000), (1, 4, 6, 70001),   # rows in global memory
+]
+
+
+@pytest.mark.parametrize("shape", EDGE_SHAPES)
+def test_random_tables_bit_exact(dp, shape):
+    K, L, S, B = shape
+    print(f"[parity] random tables K={K} L={L} S={S} B={B}", flush=True)
+    rng = np.random.default_rng(K * 1000003 + L * 10007 + S * 101 + B)
+    for variant in range(4):
+        kw = dict(tau_max=max(1, B // max(1, L // 2)))
+        if variant == 1:
+            kw.update(integer_err=3)                        # ties everywhere
+        elif variant == 2:
+            kw.update(zero_tau_frac=0.2, over_budget_frac=0.2, inf_err_frac=0.1)
+        elif variant == 3:
+            kw.update(integer_err=2, zero_tau_frac=0.3, tau_max=max(1, B // (2 * L) + 1))
+        tau, err, _ = workloads.random_instance(rng, K, L, S, B, **kw)
+        p_gpu, c_gpu, ws = gpu_solve(dp, tau, err, B)
+        p_ref, c_ref = oracle.solve_ref(tau, err, B)
+        assert_same(p_gpu, c_gpu, p_ref, c_ref, f"{shape} variant {variant}")
+        check_tables(dp, tau, err[K - 1], B, ws, K - 1, K)
+
+
+def test_infeasible_and_mixed_batches(dp):
+    # candidate 0 feasible, candidate 1 has every level of layer 2 forbidden, budget too small
+    tau = np.array([[5, 3, 1], [4, 2, 1], [6, 2, 2]], dtype=np.int32)
+    err = np.array([[[0, 1, 2], [0, 1, 2], [0, 1, 2]],
+                    [[0, 1, 2], [0, 1, 2], [np.inf, np.inf, np.inf]]], dtype=np.float32)
+    for B in (0, 3, 4, 9, 15, 200):
+        p_gpu, c_gpu, _ = gpu_solve(dp, tau, err, B)
+        p_ref, c_ref = oracle.solve_ref(tau, err, B)
+        assert_same(p_gpu, c_gpu, p_ref, c_ref, f"B={B}")
+        assert np.isinf(c_gpu[1]) and (p_gpu[1] == -1).all()
+
+
+def test_negative_zero_and_subnormal_errors(dp):
+    tiny = np.float32(1e-45)
+    tau = np.array([[1, 0], [1, 0], [2, 0]], dtype=np.int32)
+    err = np.array([[[0, tiny], [0, tiny], [0, tiny]],
+                    [[-0.0, 1], [-0.0, 1], [-0.0, 1]],
+                    [[1, -0.0], [-0.0, 0.0], [0.0, -0.0]],
+                    [[-1, 2], [3, -2.5], [0.5, -0.0]]], dtype=np.float32)
+    for B in (0, 1, 2, 4, 70):
+        p_gpu, c_gpu, _ = gpu_solve(dp, tau, err, B)
+        p_ref, c_ref = oracle.solve_ref(tau, err, B)
+        assert_same(p_gpu, c_gpu, p_ref, c_ref, f"B={B}")
+
+
+def test_stages_equal_the_fused_call_and_streams(dp):
+    cfg = workloads.CONFIGS["rn50_k1"]
+    tau, err, B = workloads.generate(cfg, K=5)
+    dev = torch.device("cuda:0")
+    tau_d, err_d = torch.from_numpy(tau).to(dev), torch.from_numpy(err).to(dev)
+    K, L, S = err.shape
+    ws = dp.alloc_workspace(K, L, S, B, dev)
+    cost = torch.empty(K, dtype=torch.float32, device=dev)
+    profile = torch.empty((K, L), dtype=torch.int16, device=dev)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        dp.spdy_dp_fill(tau_d, err_d, B, cost, ws)
+        dp.spdy_dp_backtrace(tau_d, K, B, profile, ws)
+    side.synchronize()
+    p_ref, c_ref = oracle.solve_ref(tau, err, B)
+    assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, "staged, side stream")
+    p2, c2, _ = gpu_solve(dp, tau, err, B)
+    assert_same(p2, c2, p_ref, c_ref, "fused")
+
+
+def test_workspace_too_small_is_an_error(dp):
+    dev = torch.device("cuda:0")
+    tau = torch.ones((2, 2), dtype=torch.int32, device=dev)
+    err = torch.zeros((1, 2, 2), dtype=torch.float32, device=dev)
+    ws = torch.empty(16, dtype=torch.uint8, device=dev)
+    with pytest.raises(dp.SpdyDpError) as e:
+        dp.spdy_dp_solve_batched(tau, err, 100, workspace=ws)
+    assert e.value.status == -4
