@@ -24,13 +24,28 @@ if ROOT not in sys.path:
 # figure is this number x 2 for fused multiply-add x 2 for packed fp32; neither applies to an
 # add / compare / select chain.)
 ALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
-# One update of Alg. 1's inner loop: fp32 add, fp32 compare, select of the value, select of the level.
-LANE_OPS_PER_UPDATE = 4
+# One update of Alg. 1's inner loop: an fp32 add and an fp32 min when D itself is recorded;
+# an fp32 add, a compare and two selects (value, level) when the level is tracked per cell.
+LANE_OPS_PER_UPDATE = {"d": 2, "level": 4}
+# LDS: one 4-byte read of the shifted previous row per update; 128 bytes per clock per compute
+# unit for 32-bit reads (64 lanes in two clocks).
+LDS_PEAK_BYTES = 256 * 128 * 2.4e9
+LDS_BYTES_PER_UPDATE = 4
 
 
 def executed_updates_per_candidate(tau: np.ndarray, B: int) -> int:
-    """Inner-loop trips of Alg. 1 for one candidate: level s of layer l visits t = tau..B."""
-    return int(np.clip(B + 1 - tau.astype(np.int64), 0, None).sum())
+    """Inner-loop trips of Alg. 1 on the table the device actually fills: times reduced by each
+    layer's minimum (budget B - M) and rows cut at the largest reachable reduced time.  Level s
+    of layer l then visits t' = shift .. top_l."""
+    t = tau.astype(np.int64)
+    mn = t.min(axis=1)
+    bp = B - int(mn.sum())
+    if bp < 0:
+        return 0
+    delta = t - mn[:, None]
+    span = np.where(delta <= bp, delta, 0).max(axis=1)
+    top = np.minimum(np.cumsum(span), bp)
+    return int(np.clip(top[:, None] + 1 - delta, 0, None).sum())
 
 
 def main() -> int:
@@ -39,6 +54,8 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="rn50_k1024")
+    ap.add_argument("--record", choices=["d", "level"], default="d",
+                    help="what the fill records per cell: fp32 D (fast) or the one-byte level")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -62,7 +79,7 @@ def main() -> int:
     dev = torch.device("cuda:0")
     tau_d = torch.from_numpy(tau).to(dev)
     err_d = torch.from_numpy(err).to(dev)
-    ws = dp.alloc_workspace(K, L, S, B, dev)
+    ws = dp.alloc_workspace(K, L, S, B, dev, compact=(args.record == "level"))
     profile = torch.empty((K, L), dtype=torch.int16, device=dev)
     cost = torch.empty((K,), dtype=torch.float32, device=dev)
 
@@ -73,7 +90,7 @@ def main() -> int:
         dp.spdy_dp_fill(tau_d, err_d, B, cost, ws)
         if ev_b is not None:
             ev_b.record()
-        dp.spdy_dp_backtrace(tau_d, K, B, profile, ws)
+        dp.spdy_dp_backtrace(tau_d, err_d, B, profile, cost, ws)
 
     for _ in range(args.warmup):
         step()
@@ -93,7 +110,9 @@ def main() -> int:
     nominal = cfg.cell_updates                       # K*L*S*B
     executed = K * executed_updates_per_candidate(tau, B)
     value = nominal / (ms_per_step * 1e-3)
-    achieved = executed * LANE_OPS_PER_UPDATE / (fill_ms * 1e-3)
+    ops = LANE_OPS_PER_UPDATE[args.record]
+    achieved = executed * ops / (fill_ms * 1e-3)
+    lds_achieved = executed * LDS_BYTES_PER_UPDATE / (fill_ms * 1e-3)
 
     p_gpu = profile.cpu().numpy()
     c_gpu = cost.cpu().numpy()
@@ -112,7 +131,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": cfg.name, "K": K, "L": L, "S": S, "B": B,
+        "config": {"workload": cfg.name, "K": K, "L": L, "S": S, "B": B, "record": args.record,
                    "executed_updates": executed, "nominal_updates": nominal},
         "roofline": {
             "bound": "alu",
@@ -121,8 +140,15 @@ def main() -> int:
             "peak": ALU_PEAK_LANE_OPS / 1e12,
             "unit": "Tlane-op/s",
             "frac": achieved / ALU_PEAK_LANE_OPS,
+            "lane_ops_per_update": ops,
             "kernel_ms": fill_ms,
             "traffic": None,
+        },
+        "roofline_lds": {
+            "achieved": lds_achieved / 1e12,
+            "peak": LDS_PEAK_BYTES / 1e12,
+            "unit": "TB/s",
+            "frac": lds_achieved / LDS_PEAK_BYTES,
         },
     }
 

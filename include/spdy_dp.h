@@ -25,6 +25,20 @@
  *   - a level with tau > B, or with err = +inf, is never chosen; tau = 0 is legal;
  *   - a candidate that no profile satisfies gets cost = +inf and profile = -1 (status stays OK).
  *
+ * Two exact reductions of Alg. 1's table are applied on the device (results are unchanged):
+ *   - every layer's smallest time m_l = min_s tau[l][s] is subtracted from that layer's times
+ *     and M = sum_l m_l from the budget, so layer l's row only spans t' = t - (m_0 + .. + m_l)
+ *     in [0, B - M] (cells outside can never lie on a profile that meets the budget);
+ *   - cells beyond the largest time reachable after l layers are +inf and are not computed.
+ *
+ * What is recorded per cell for the walk back depends on the workspace the caller provides:
+ *   - spdy_dp_workspace_bytes():     D itself (fp32 per cell); the fill then needs only an add
+ *     and a min per update, and the walk back re-derives the level of the L cells on the path
+ *     (smallest s with D_{l-1}[t - tau[l][s]] + err[k][l][s] == D_l[t]);
+ *   - spdy_dp_workspace_bytes_min(): the level P of Alg. 1 (one byte per cell, 4x smaller; the
+ *     fill tracks the level with a compare and two selects per update).
+ * Both give the same profile and cost, bit for bit.
+ *
  * Conventions for every entry point:
  *   - tau, err, profile, cost, workspace are DEVICE pointers, C-contiguous, owned by the caller.
  *     The library allocates nothing, frees nothing and never synchronises: work is enqueued on
@@ -49,18 +63,20 @@ extern "C" {
 #define SPDY_DP_OK 0
 #define SPDY_DP_ERR_NULL (-1)      /* a required pointer is NULL                              */
 #define SPDY_DP_ERR_DIM (-2)       /* K, L or S <= 0, or B < 0                                 */
-#define SPDY_DP_ERR_LEVELS (-3)    /* S > 255: the per-cell level record is one byte, 0xFF =
-                                      "no level reaches this cell"                              */
-#define SPDY_DP_ERR_WORKSPACE (-4) /* workspace_bytes < spdy_dp_workspace_bytes(K, L, S, B)    */
+#define SPDY_DP_ERR_LEVELS (-3)    /* S > 255: a recorded level is one byte, 0xFF = "no level
+                                      reaches this cell"                                        */
+#define SPDY_DP_ERR_WORKSPACE (-4) /* workspace_bytes < spdy_dp_workspace_bytes_min(K,L,S,B)   */
 #define SPDY_DP_ERR_OVERFLOW (-5)  /* K * L * (B + 1) does not fit the index arithmetic         */
 #define SPDY_DP_ERR_LAUNCH (-9)    /* the HIP runtime refused a launch (see hipGetLastError)    */
 
-/* Bytes of device workspace spdy_dp_solve_batched / spdy_dp_fill need for these sizes, or 0 if
- * the sizes are invalid (see the status codes above).  The workspace holds the per-cell level
- * record P of Alg. 1 (one byte per (k, l, t), rows padded to a multiple of 64 buckets), the
- * final time t* per candidate, and -- when two D rows of B + 1 floats do not fit the 160 KB
- * of LDS of one compute unit -- two D rows per candidate. */
+/* Bytes of device workspace for the fast variant (fp32 D recorded per cell), or 0 if the sizes
+ * are invalid.  About 4 * K * (L + 1) * (B + 1) bytes. */
 size_t spdy_dp_workspace_bytes(int K, int L, int S, int B);
+
+/* Smallest workspace accepted (one-byte level record per cell), or 0 if the sizes are invalid.
+ * About K * L * (B + 1) bytes, plus 8 * K * (B + 1) when two rows of B + 1 floats exceed the
+ * 160 KB of LDS of a compute unit.  Any size in between selects this variant too. */
+size_t spdy_dp_workspace_bytes_min(int K, int L, int S, int B);
 
 /* Solve all K candidates: the whole of Alg. 1 (table fill, final argmin over t, walk back).
  *   tau      in  int32 [L][S]     times in buckets, >= 0, shared by all candidates
@@ -72,23 +88,34 @@ int spdy_dp_solve_batched(const int32_t *tau, const float *err, int K, int L, in
                           int16_t *profile, float *cost, void *workspace, size_t workspace_bytes,
                           void *stream);
 
-/* First part of Alg. 1: fills the tables layer by layer (Eq. 2-3), records the chosen level of
- * every cell in the workspace, and takes the final argmin over t <= B.  Writes cost[k] and keeps
- * t*[k] in the workspace for spdy_dp_backtrace. */
+/* First part of Alg. 1: fills the tables layer by layer (Eq. 2-3), records D or the chosen level
+ * of every computed cell in the workspace, and takes the final argmin over t <= B.  Writes
+ * cost[k] (compares equal to the final cost; spdy_dp_backtrace rewrites it) and keeps t*[k] in
+ * the workspace. */
 int spdy_dp_fill(const int32_t *tau, const float *err, int K, int L, int S, int B, float *cost,
                  void *workspace, size_t workspace_bytes, void *stream);
 
-/* Last loop of Alg. 1: walks the recorded levels back from (L-1, t*[k]) and writes profile[k].
- * `workspace` must be the one a spdy_dp_fill call with the same K, L, S, B and tau has filled
- * earlier on the same stream (or on a stream already synchronised with it). */
-int spdy_dp_backtrace(const int32_t *tau, int K, int L, int S, int B, int16_t *profile,
-                      const void *workspace, size_t workspace_bytes, void *stream);
+/* Last loop of Alg. 1: walks back from (L-1, t*[k]) and writes profile[k] and cost[k].
+ * `workspace` (same size) must be the one a spdy_dp_fill call with the same tau, err, K, L, S, B
+ * has filled earlier on the same stream (or on a stream already synchronised with it). */
+int spdy_dp_backtrace(const int32_t *tau, const float *err, int K, int L, int S, int B,
+                      int16_t *profile, float *cost, const void *workspace,
+                      size_t workspace_bytes, void *stream);
 
-/* Debug/test accessors describing the workspace layout for given sizes: byte offset of the
- * level record P, its row pitch in bytes (P[k][l][t] is at offset + ((k*L + l)*pitch + t)), and
- * the byte offset of the int32 t*[K] array.  Return SPDY_DP_OK or a size error. */
-int spdy_dp_workspace_layout(int K, int L, int S, int B, size_t *choice_offset,
-                             size_t *choice_pitch, size_t *tstar_offset);
+/* Test/debug accessor: where things are in a workspace of `workspace_bytes` bytes.
+ *   out[0] variant: 0 = fp32 D record, 1 = one-byte level record
+ *   out[1] byte offset of the int32 header: [0] B - M (or -1 if M > B: nobody is feasible),
+ *          [1] M, [2] reduced row length (B - M + 1 padded to 64), [3] 1 if two reduced rows fit
+ *          LDS; then m_l at [8 + l] and the number of computed 64-bucket chunks of layer l at
+ *          [8 + L + l]
+ *   out[2] byte offset of int32 t*[K] (reduced time t* - M, or -1 if infeasible)
+ *   out[3] byte offset of the record
+ *   out[4] record pitch in elements (buckets per row, a multiple of 64)
+ *   out[5] record rows per candidate: L + 1 for the D record (row l + 1 holds layer l, row 0 the
+ *          state before the first layer when rows live in global memory), L for the level record
+ * Element (k, r, t') of the record is at out[3] + ((k * out[5] + r) * out[4] + t') * elemsize.
+ * Returns SPDY_DP_OK or a size / workspace error. */
+int spdy_dp_workspace_layout(int K, int L, int S, int B, size_t workspace_bytes, size_t out[6]);
 
 /* Static, human-readable text for a status code. */
 const char *spdy_dp_strerror(int status);

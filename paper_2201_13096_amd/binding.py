@@ -17,8 +17,8 @@ _lib = None
 OK = 0
 ERR_NULL, ERR_DIM, ERR_LEVELS, ERR_WORKSPACE, ERR_OVERFLOW, ERR_LAUNCH = -1, -2, -3, -4, -5, -9
 
-EXPORTS = ("spdy_dp_workspace_bytes", "spdy_dp_solve_batched", "spdy_dp_fill",
-           "spdy_dp_backtrace", "spdy_dp_workspace_layout", "spdy_dp_strerror")
+EXPORTS = ("spdy_dp_workspace_bytes", "spdy_dp_workspace_bytes_min", "spdy_dp_solve_batched",
+           "spdy_dp_fill", "spdy_dp_backtrace", "spdy_dp_workspace_layout", "spdy_dp_strerror")
 
 
 class SpdyDpError(RuntimeError):
@@ -39,15 +39,16 @@ def lib() -> ctypes.CDLL:
         vp, i, sz = ctypes.c_void_p, ctypes.c_int, ctypes.c_size_t
         L.spdy_dp_workspace_bytes.restype = sz
         L.spdy_dp_workspace_bytes.argtypes = [i, i, i, i]
+        L.spdy_dp_workspace_bytes_min.restype = sz
+        L.spdy_dp_workspace_bytes_min.argtypes = [i, i, i, i]
         L.spdy_dp_solve_batched.restype = i
         L.spdy_dp_solve_batched.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, sz, vp]
         L.spdy_dp_fill.restype = i
         L.spdy_dp_fill.argtypes = [vp, vp, i, i, i, i, vp, vp, sz, vp]
         L.spdy_dp_backtrace.restype = i
-        L.spdy_dp_backtrace.argtypes = [vp, i, i, i, i, vp, vp, sz, vp]
+        L.spdy_dp_backtrace.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, sz, vp]
         L.spdy_dp_workspace_layout.restype = i
-        L.spdy_dp_workspace_layout.argtypes = [i, i, i, i, ctypes.POINTER(sz), ctypes.POINTER(sz),
-                                               ctypes.POINTER(sz)]
+        L.spdy_dp_workspace_layout.argtypes = [i, i, i, i, sz, ctypes.POINTER(sz)]
         L.spdy_dp_strerror.restype = ctypes.c_char_p
         L.spdy_dp_strerror.argtypes = [i]
         _lib = L
@@ -62,14 +63,20 @@ def spdy_dp_workspace_bytes(K: int, L: int, S: int, B: int) -> int:
     return int(lib().spdy_dp_workspace_bytes(K, L, S, B))
 
 
-def spdy_dp_workspace_layout(K: int, L: int, S: int, B: int):
-    """(choice_offset, choice_pitch, tstar_offset) in bytes."""
-    a, b, c = ctypes.c_size_t(), ctypes.c_size_t(), ctypes.c_size_t()
-    st = lib().spdy_dp_workspace_layout(K, L, S, B, ctypes.byref(a), ctypes.byref(b),
-                                        ctypes.byref(c))
+def spdy_dp_workspace_bytes_min(K: int, L: int, S: int, B: int) -> int:
+    return int(lib().spdy_dp_workspace_bytes_min(K, L, S, B))
+
+
+def spdy_dp_workspace_layout(K: int, L: int, S: int, B: int, workspace_bytes: int) -> dict:
+    """Where things are in a workspace of that size (see the header): variant (0 = fp32 D
+    record, 1 = one-byte level record), byte offsets, record pitch and rows per candidate."""
+    out = (ctypes.c_size_t * 6)()
+    st = lib().spdy_dp_workspace_layout(K, L, S, B, int(workspace_bytes), out)
     if st != OK:
         raise SpdyDpError(st)
-    return a.value, b.value, c.value
+    keys = ("variant", "meta_offset", "tstar_offset", "record_offset", "record_pitch",
+            "record_rows")
+    return dict(zip(keys, (int(v) for v in out)))
 
 
 def _dev(t: torch.Tensor, dtype, name: str) -> torch.Tensor:
@@ -93,12 +100,12 @@ def _stream(stream) -> int:
     return int(stream.cuda_stream)
 
 
-def alloc_workspace(K: int, L: int, S: int, B: int, device=None) -> torch.Tensor:
-    n = spdy_dp_workspace_bytes(K, L, S, B)
+def alloc_workspace(K: int, L: int, S: int, B: int, device=None, compact: bool = False):
+    """Workspace tensor: the fast fp32-record size, or the 4x smaller level-record size."""
+    n = (spdy_dp_workspace_bytes_min if compact else spdy_dp_workspace_bytes)(K, L, S, B)
     if n == 0:
-        raise SpdyDpError(lib().spdy_dp_workspace_layout(
-            K, L, S, B, ctypes.byref(ctypes.c_size_t()), ctypes.byref(ctypes.c_size_t()),
-            ctypes.byref(ctypes.c_size_t())))
+        raise SpdyDpError(lib().spdy_dp_workspace_layout(K, L, S, B, 2 ** 62,
+                                                         (ctypes.c_size_t * 6)()))
     return torch.empty(n, dtype=torch.uint8, device=device or "cuda")
 
 
@@ -137,12 +144,15 @@ def spdy_dp_fill(tau, err, B: int, cost, workspace, stream=None) -> None:
         raise SpdyDpError(st)
 
 
-def spdy_dp_backtrace(tau, K: int, B: int, profile, workspace, stream=None) -> None:
+def spdy_dp_backtrace(tau, err, B: int, profile, cost, workspace, stream=None) -> None:
     tau = _dev(tau, torch.int32, "tau")
-    L, S = (int(x) for x in tau.shape)
+    err = _dev(err, torch.float32, "err")
+    K, L, S = _shapes(tau, err)
     _dev(profile, torch.int16, "profile")
+    _dev(cost, torch.float32, "cost")
     _dev(workspace, torch.uint8, "workspace")
-    st = lib().spdy_dp_backtrace(tau.data_ptr(), int(K), L, S, int(B), profile.data_ptr(),
-                                 workspace.data_ptr(), workspace.numel(), _stream(stream))
+    st = lib().spdy_dp_backtrace(tau.data_ptr(), err.data_ptr(), K, L, S, int(B),
+                                 profile.data_ptr(), cost.data_ptr(), workspace.data_ptr(),
+                                 workspace.numel(), _stream(stream))
     if st != OK:
         raise SpdyDpError(st)

@@ -5,21 +5,28 @@
 //
 // Mapping.  Alg. 1's triple loop (layer, level, time) is a min-plus recurrence with no reuse of a
 // D_{l-1} element across levels (every level shifts the row by a different tau), so there is no
-// contraction to put on the matrix cores: the work is one LDS read, one fp32 add, one compare
-// and two selects per (l, s, t).  The remark after Alg. 1 (vectorise over t by shifting the row)
-// is what the lanes do here:
+// contraction to put on the matrix cores: the work per (l, s, t) is one LDS read, one fp32 add
+// and a min (plus a compare and selects when the level itself is tracked).  The remark after
+// Alg. 1 (vectorise over t by shifting the row) is what the lanes do here:
+//   * a prepare kernel subtracts each layer's smallest time from the layer and from the budget
+//     (rows shrink to B - M + 1 buckets) and bounds the reachable part of each row;
 //   * one workgroup owns one candidate; its two live D rows (previous / current layer) stay in
 //     LDS for the whole solve and swap roles after every layer (one barrier per layer);
 //   * the time axis is cut into chunks of 64 buckets; lane i of a wave works on bucket
 //     64*c + i of a chunk, so every ds_read_b32 of the shifted row touches 64 consecutive
-//     dwords (conflict-free for any shift) and every store of the level record is 64
-//     consecutive bytes;
-//   * a wave keeps R chunks in registers (running minimum and level for R buckets per lane) and
-//     sweeps the levels once, with tau[l][s] and err[k][l][s] held in scalar registers;
-//   * per (wave, level) the shift is classified with scalar compares: entirely left of the row
-//     (skipped), entirely inside (no per-lane bounds test), or straddling t = tau (per-lane test).
-// When two rows do not fit in LDS the same per-group routine runs from per-layer launches with
-// the rows in global memory (they stay in L2 / Infinity Cache between consecutive layers).
+//     dwords (conflict-free for any shift) and every store of the record is 64 consecutive
+//     elements;
+//   * a wave keeps R chunks in registers (running minimum, and the level when tracked, for R
+//     buckets per lane) and sweeps the levels once; (shift, error) pairs of a layer are staged
+//     per candidate, sorted by shift when only the minimum is needed, and fetched eight at a
+//     time with one scalar load;
+//   * each LDS row has a +inf apron of one group width on its left, so a level whose shift
+//     falls inside the group needs no per-lane bounds test; levels whose shift lies beyond the
+//     group are skipped with a scalar compare;
+//   * a workgroup of 16 waves is split at run time into teams, one candidate per team, so that
+//     each wave owns about ten chunks whatever the reduced row length is.
+// When two reduced rows do not fit in LDS a per-group routine with per-lane bounds tests runs
+// from per-layer launches with the rows in global memory.
 #include <hip/hip_runtime.h>
 
 #include <stdint.h>
@@ -31,27 +38,53 @@ namespace {
 constexpr int kWave = 64;            // lanes per wavefront = buckets per chunk
 constexpr int kMaxGroup = 10;        // most chunks a wave keeps in registers at once
 constexpr int kResidentThreads = 1024;
+constexpr int kResidentWaves = kResidentThreads / kWave;
 constexpr int kStreamThreads = 256;  // per-layer kernel: 4 waves per workgroup
 constexpr int kStreamGroup = 8;      // chunks per wave in the per-layer kernel
-constexpr size_t kLdsBytes = 160 * 1024;
+constexpr int kLdsBytes = 160 * 1024;
+constexpr int kLdsHalf = kLdsBytes / 2;   // lets two workgroups share a compute unit
+constexpr int kHalo = kMaxGroup * kWave;  // +inf apron left of every LDS row (one group width)
+constexpr int kBatch = 8;                 // levels fetched per scalar load
 constexpr unsigned kNoLevel = 0xFF;
 constexpr size_t kAlign = 256;
+constexpr int kMetaHeader = 8;       // int32 words before the per-layer arrays
+
+// kMetaPath: 0 = per-layer kernels, 1 / 2 = LDS-resident kernel launched with the smaller /
+// larger LDS allocation.  kMetaTeamWaves x kMetaTeams <= waves of a resident workgroup.
+enum MetaWord {
+    kMetaBudget = 0, kMetaMinTime = 1, kMetaRow = 2, kMetaPath = 3, kMetaTeamWaves = 4,
+    kMetaTeams = 5
+};
+
+struct LevelPair {   // one level of one layer of one candidate, as the resident kernel reads it
+    int32_t shift;   // tau[l][s] - m_l  (INT32_MAX in padding entries)
+    float err;
+};
+
+enum Variant { kValueRecord = 0, kLevelRecord = 1 };
 
 // ---------------------------------------------------------------------------------------------
 // Workspace layout (host side, shared by every entry point)
 struct Layout {
     int status;
-    size_t row;          // buckets per padded row (multiple of 64)
-    size_t choice_off;   // uint8 P[K][L][row]
+    int variant;
+    size_t row;          // buckets per padded row for the full budget (multiple of 64)
+    bool may_stream;     // two rows of the full budget exceed LDS: the per-layer path may run
+    size_t meta_off;     // int32 meta[kMetaHeader + 2 L]
     size_t tstar_off;    // int32 tstar[K]
-    size_t drows_off;    // float D[2][K][row], only when !resident
-    size_t total;
-    bool resident;       // two D rows fit in LDS
+    size_t s8;           // levels per layer padded to a multiple of kBatch
+    size_t order_off;    // uint8 order[L][S]: level visited r-th in layer l
+    size_t pairs_off;    // LevelPair pairs[K][L][s8]
+    size_t record_off;   // float D[K][L+1][row]  or  uint8 P[K][L][row]
+    size_t rows_off;     // float D[2][K][row], level record with may_stream only
+    size_t total_value;  // bytes needed by the D-record variant
+    size_t total_level;  // bytes needed by the level-record variant
 };
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-Layout make_layout(int K, int L, int S, int B)
+// `workspace_bytes` selects the variant; pass SIZE_MAX to get the sizes only.
+Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes)
 {
     Layout lay{};
     if (K <= 0 || L <= 0 || S <= 0 || B < 0) {
@@ -67,30 +100,308 @@ Layout make_layout(int K, int L, int S, int B)
         return lay;
     }
     lay.row = align_up((size_t)B + 1, kWave);
-    // K * L * row and 2 * K * row * 4 must fit size_t with room to spare
-    const unsigned __int128 cells = (unsigned __int128)K * (unsigned __int128)L * lay.row;
-    const unsigned __int128 drows = (unsigned __int128)2 * K * lay.row * sizeof(float);
-    if (cells + drows + (unsigned __int128)K * 4 + 4 * kAlign > (unsigned __int128)1 << 62) {
+    const unsigned __int128 cells = (unsigned __int128)K * ((unsigned __int128)L + 1) * lay.row;
+    if (cells * sizeof(float) + (unsigned __int128)K * L * 2048 + (unsigned __int128)K * 16 +
+            (unsigned __int128)L * 512 >
+        (unsigned __int128)1 << 62) {
         lay.status = SPDY_DP_ERR_OVERFLOW;
         return lay;
     }
-    lay.resident = 2 * lay.row * sizeof(float) <= kLdsBytes;
-    lay.choice_off = 0;
-    lay.tstar_off = align_up((size_t)cells, kAlign);
-    lay.drows_off = align_up(lay.tstar_off + (size_t)K * sizeof(int32_t), kAlign);
-    lay.total = lay.resident ? lay.drows_off : lay.drows_off + (size_t)drows;
+    lay.may_stream = 2 * (lay.row + kHalo) * sizeof(float) > (size_t)kLdsBytes;
+    lay.s8 = align_up((size_t)S, kBatch);
+    lay.meta_off = 0;
+    lay.tstar_off = align_up((kMetaHeader + 2 * (size_t)L) * sizeof(int32_t), kAlign);
+    lay.order_off = align_up(lay.tstar_off + (size_t)K * sizeof(int32_t), kAlign);
+    lay.pairs_off = align_up(lay.order_off + (size_t)L * S, kAlign);
+    lay.record_off =
+        align_up(lay.pairs_off + (size_t)K * L * lay.s8 * sizeof(LevelPair), kAlign);
+    lay.total_value = lay.record_off + (size_t)K * ((size_t)L + 1) * lay.row * sizeof(float);
+    lay.rows_off = align_up(lay.record_off + (size_t)K * L * lay.row, kAlign);
+    lay.total_level =
+        lay.may_stream ? lay.rows_off + 2 * (size_t)K * lay.row * sizeof(float) : lay.rows_off;
+    if (workspace_bytes >= lay.total_value)
+        lay.variant = kValueRecord;
+    else if (workspace_bytes >= lay.total_level)
+        lay.variant = kLevelRecord;
+    else {
+        lay.status = SPDY_DP_ERR_WORKSPACE;
+        return lay;
+    }
     lay.status = SPDY_DP_OK;
     return lay;
 }
 
 // ---------------------------------------------------------------------------------------------
-// One group of R chunks (R*64 consecutive buckets starting at t0) of one layer.
-// prev / cur: the two D rows (LDS or global); choice: this layer's row of the level record.
-// tau_l / err_l: the S times and errors of this layer for this candidate (wave-uniform).
-template <int R>
+// Prepare: per-layer smallest time m_l, M = sum m_l, reduced budget B - M, and how many 64-bucket
+// chunks of each reduced row can hold a finite value (largest reachable reduced time after
+// layer l is sum_{j<=l} max_s (tau[j][s] - m_j) over the levels that fit the reduced budget).
+// It also picks the path: which launch of the resident kernel (LDS allocation lds_small or
+// lds_large bytes, `waves` waves per workgroup) fits, and into how many teams its waves split.
+__global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ tau, int L, int S,
+                                                  int B, int waves, int lds_small, int lds_large,
+                                                  int32_t *__restrict__ meta)
+{
+    __shared__ int s_budget;
+    const int tid = threadIdx.x, n = blockDim.x;
+    int32_t *mn = meta + kMetaHeader;
+    int32_t *nact = meta + kMetaHeader + L;
+    for (int l = tid; l < L; l += n) {
+        int m = INT32_MAX;
+        for (int s = 0; s < S; ++s)
+            m = min(m, tau[(size_t)l * S + s]);
+        mn[l] = m;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        long long M = 0;
+        for (int l = 0; l < L; ++l)
+            M += mn[l];
+        const int bp = (M > B) ? -1 : (int)(B - M);
+        const int rowp = bp < 0 ? 0 : (bp + kWave) / kWave * kWave;
+        meta[kMetaBudget] = bp;
+        meta[kMetaMinTime] = M > INT32_MAX ? INT32_MAX : (int)M;
+        meta[kMetaRow] = rowp;
+        const long long team_lds = 2 * ((long long)rowp + kHalo) * (long long)sizeof(float);
+        int path = 0, lds = 0;
+        if (bp < 0 || team_lds <= lds_small) {   // an infeasible table is reported by path 1
+            path = 1;
+            lds = lds_small;
+        } else if (team_lds <= lds_large) {
+            path = 2;
+            lds = lds_large;
+        }
+        // teams: as many candidates per workgroup as keeps about kMaxGroup chunks per wave
+        int teams = 1;
+        if (path != 0 && bp >= 0) {
+            const int want = (rowp / kWave + kMaxGroup - 1) / kMaxGroup;   // waves per candidate
+            teams = waves / (want < 1 ? 1 : want);
+            const long long fit = lds / team_lds;
+            if (teams > fit)
+                teams = (int)fit;
+            if (teams < 1)
+                teams = 1;
+        }
+        meta[kMetaPath] = path;
+        meta[kMetaTeams] = teams;
+        meta[kMetaTeamWaves] = waves / teams;
+        s_budget = bp;
+    }
+    __syncthreads();
+    const int bp = s_budget;
+    for (int l = tid; l < L; l += n) {
+        int span = 0;
+        if (bp >= 0) {
+            const int m = mn[l];
+            for (int s = 0; s < S; ++s) {
+                const long long d = (long long)tau[(size_t)l * S + s] - m;
+                if (d <= bp)
+                    span = max(span, (int)d);
+            }
+        }
+        nact[l] = span;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        long long h = 0;
+        for (int l = 0; l < L; ++l) {
+            h += nact[l];
+            const long long top = h < bp ? h : bp;
+            nact[l] = bp < 0 ? 0 : (int)((top + kWave) / kWave);
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Visiting order of the levels of each layer.  When only the minimum is needed (D record) the
+// levels are sorted by shift, ties by index, so the levels a group of buckets can use form a
+// prefix; when the level itself is tracked the order stays ascending in s (ties go to the
+// smallest s through the strict "<").  One workgroup per layer, one thread per level.
+__global__ __launch_bounds__(256) void dp_order_levels(const int32_t *__restrict__ tau, int S,
+                                                       int sorted, uint8_t *__restrict__ order)
+{
+    const int l = blockIdx.x, s = threadIdx.x;
+    if (s >= S)
+        return;
+    int rank = s;
+    if (sorted) {
+        const int32_t *tau_l = tau + (size_t)l * S;
+        const int mine = tau_l[s];
+        rank = 0;
+        for (int o = 0; o < S; ++o) {
+            const int other = tau_l[o];
+            rank += (other < mine || (other == mine && o < s)) ? 1 : 0;
+        }
+    }
+    order[(size_t)l * S + rank] = (uint8_t)s;
+}
+
+// pairs[k][l][r] = (tau[l][s] - m_l, err[k][l][s]) for s = order[l][r]; padding up to s8 is
+// (INT32_MAX, +inf), which no group of buckets can use.
+__global__ __launch_bounds__(256) void dp_stage_levels(const int32_t *__restrict__ tau,
+                                                       const float *__restrict__ err,
+                                                       const int32_t *__restrict__ meta,
+                                                       const uint8_t *__restrict__ order, int K,
+                                                       int L, int S, int s8,
+                                                       LevelPair *__restrict__ pairs)
+{
+    const size_t n = (size_t)K * L * s8;
+    const int32_t *mn = meta + kMetaHeader;
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (size_t)gridDim.x * blockDim.x) {
+        const int r = (int)(i % s8);
+        const size_t kl = i / s8;
+        const int l = (int)(kl % L);
+        LevelPair p;
+        p.shift = INT32_MAX;
+        p.err = __builtin_inff();
+        if (r < S) {
+            const int s = order[(size_t)l * S + r];
+            p.shift = tau[(size_t)l * S + s] - mn[l];
+            p.err = err[kl * S + s];
+        }
+        pairs[i] = p;
+    }
+}
+
+// v_min_f32 / v_min3_f32 without the canonicalising v_max the compiler puts in front of fminf
+// (no NaN can occur: err is finite or +inf and D starts at -0 / +inf).
+__device__ __forceinline__ void vmin(float &b, float x)
+{
+    asm("v_min_f32 %0, %0, %1" : "+v"(b) : "v"(x));
+}
+__device__ __forceinline__ void vmin3(float &b, float x, float y)
+{
+    asm("v_min3_f32 %0, %0, %1, %2" : "+v"(b) : "v"(x), "v"(y));
+}
+
+// Resident path: one group of R chunks (R*64 consecutive reduced buckets from t0) of one layer.
+//   prev / cur : LDS rows, prev[-kHalo .. -1] reads +inf
+//   pairs_l    : the layer's s8 staged levels (64-byte aligned), sorted by shift unless kLevel
+//   order_l    : level index of the r-th staged level (kLevel only: the identity)
+template <int R, bool kLevel>
+__device__ __forceinline__ void fill_group_lds(const float *__restrict__ prev,
+                                               float *__restrict__ cur,
+                                               uint8_t *__restrict__ choice,
+                                               float *__restrict__ rec,
+                                               const LevelPair *__restrict__ pairs_l, int s8,
+                                               int t0, int lane)
+{
+    float best[R];
+    unsigned arg[R];
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        best[j] = __builtin_inff();
+        arg[j] = kNoLevel;
+    }
+    const int last = t0 + R * kWave - 1;      // last bucket of the group
+    const char *pl = reinterpret_cast<const char *>(prev + t0 + lane);
+    const LevelPair *pp =
+        static_cast<const LevelPair *>(__builtin_assume_aligned(pairs_l, kBatch * 8));
+
+    auto sweep = [&]() {
+        for (int s0 = 0; s0 < s8; s0 += kBatch) {
+            int ts[kBatch];
+            float es[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                ts[i] = pp[s0 + i].shift;
+                es[i] = pp[s0 + i].err;
+            }
+            if constexpr (kLevel) {
+#pragma unroll
+                for (int i = 0; i < kBatch; ++i) {
+                    if (ts[i] > last)
+                        continue;             // every lane would read left of the apron
+                    const float *p =
+                        reinterpret_cast<const float *>(pl - (size_t)((unsigned)ts[i] * 4u));
+                    const unsigned s = (unsigned)(s0 + i);
+#pragma unroll
+                    for (int j = 0; j < R; ++j) {
+                        const float v = p[j * kWave] + es[i];
+                        if (v < best[j]) {
+                            best[j] = v;
+                            arg[j] = s;
+                        }
+                    }
+                }
+            } else {
+#pragma unroll
+                for (int i = 0; i < kBatch; i += 2) {
+                    if (ts[i] > last)
+                        return;               // sorted by shift: nothing further applies
+                    const float *p0 =
+                        reinterpret_cast<const float *>(pl - (size_t)((unsigned)ts[i] * 4u));
+                    if (ts[i + 1] > last) {
+#pragma unroll
+                        for (int j = 0; j < R; ++j)
+                            vmin(best[j], p0[j * kWave] + es[i]);
+                        return;
+                    }
+                    const float *p1 =
+                        reinterpret_cast<const float *>(pl - (size_t)((unsigned)ts[i + 1] * 4u));
+#pragma unroll
+                    for (int j = 0; j < R; ++j)
+                        vmin3(best[j], p0[j * kWave] + es[i], p1[j * kWave] + es[i + 1]);
+                }
+            }
+        }
+    };
+    sweep();
+
+    const int tl = t0 + lane;
+#pragma unroll
+    for (int j = 0; j < R; ++j) {
+        cur[tl + j * kWave] = best[j];
+        if constexpr (kLevel)
+            choice[tl + j * kWave] = (uint8_t)arg[j];
+        else
+            rec[tl + j * kWave] = best[j];
+    }
+}
+
+template <bool kLevel>
+__device__ __forceinline__ void fill_chunks_lds(const float *prev, float *cur, uint8_t *choice,
+                                                float *rec, const LevelPair *pairs_l, int s8,
+                                                int c, int c_end, int lane)
+{
+    while (c < c_end) {
+        const int n = c_end - c;
+        const int groups = (n + kMaxGroup - 1) / kMaxGroup;
+        const int r = (n + groups - 1) / groups;
+        const int t0 = c * kWave;
+        switch (r) {
+#define SPDY_CASE(RR)                                                                   \
+    case RR:                                                                            \
+        fill_group_lds<RR, kLevel>(prev, cur, choice, rec, pairs_l, s8, t0, lane);      \
+        break;
+            SPDY_CASE(1)
+            SPDY_CASE(2)
+            SPDY_CASE(3)
+            SPDY_CASE(4)
+            SPDY_CASE(5)
+            SPDY_CASE(6)
+            SPDY_CASE(7)
+            SPDY_CASE(8)
+            SPDY_CASE(9)
+            SPDY_CASE(10)
+#undef SPDY_CASE
+        }
+        c += r;
+    }
+}
+
+// ---------------------------------------------------------------------------------------------
+// Streamed path: one group of R chunks (R*64 consecutive reduced buckets from t0) of one layer,
+// rows in global memory, per-lane bounds test where the group straddles t = shift.
+//   prev / cur : the two D rows (LDS or global)
+//   kLevel     : track the level per cell and store it to `choice` (Alg. 1's P)
+//   kRecord    : also store the value to `rec` (the D record in global memory)
+//   tau_l / err_l : the S times and errors of this layer for this candidate (wave-uniform);
+//   mn         : the layer's smallest time, so the shift of level s is tau_l[s] - mn
+template <int R, bool kLevel, bool kRecord>
 __device__ __forceinline__ void fill_group(const float *__restrict__ prev, float *__restrict__ cur,
-                                           uint8_t *__restrict__ choice,
-                                           const int32_t *__restrict__ tau_l,
+                                           uint8_t *__restrict__ choice, float *__restrict__ rec,
+                                           const int32_t *__restrict__ tau_l, int mn,
                                            const float *__restrict__ err_l, int S, int t0,
                                            int lane)
 {
@@ -105,7 +416,7 @@ __device__ __forceinline__ void fill_group(const float *__restrict__ prev, float
     const int last = t0 + R * kWave - 1;      // last bucket of the group
 
     for (int s = 0; s < S; ++s) {
-        const int ts = tau_l[s];
+        const int ts = tau_l[s] - mn;
         const float es = err_l[s];
         if (ts > last)
             continue;                         // every lane would read left of t = 0
@@ -114,9 +425,13 @@ __device__ __forceinline__ void fill_group(const float *__restrict__ prev, float
 #pragma unroll
             for (int j = 0; j < R; ++j) {
                 const float v = p[j * kWave] + es;
-                if (v < best[j]) {
-                    best[j] = v;
-                    arg[j] = (unsigned)s;
+                if constexpr (kLevel) {
+                    if (v < best[j]) {
+                        best[j] = v;
+                        arg[j] = (unsigned)s;
+                    }
+                } else {
+                    best[j] = fminf(best[j], v);
                 }
             }
         } else {                              // the group straddles t = tau: test per lane
@@ -125,9 +440,13 @@ __device__ __forceinline__ void fill_group(const float *__restrict__ prev, float
                 const int u = tl + j * kWave - ts;
                 if (u >= 0) {
                     const float v = prev[u] + es;
-                    if (v < best[j]) {
-                        best[j] = v;
-                        arg[j] = (unsigned)s;
+                    if constexpr (kLevel) {
+                        if (v < best[j]) {
+                            best[j] = v;
+                            arg[j] = (unsigned)s;
+                        }
+                    } else {
+                        best[j] = fminf(best[j], v);
                     }
                 }
             }
@@ -136,14 +455,18 @@ __device__ __forceinline__ void fill_group(const float *__restrict__ prev, float
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         cur[tl + j * kWave] = best[j];
-        choice[tl + j * kWave] = (uint8_t)arg[j];
+        if constexpr (kLevel)
+            choice[tl + j * kWave] = (uint8_t)arg[j];
+        if constexpr (kRecord)
+            rec[tl + j * kWave] = best[j];
     }
 }
 
 // Chunks [c, c_end) of one layer, in groups of at most kMaxGroup chunks of near-equal size.
+template <bool kLevel, bool kRecord>
 __device__ __forceinline__ void fill_chunks(const float *prev, float *cur, uint8_t *choice,
-                                            const int32_t *tau_l, const float *err_l, int S,
-                                            int c, int c_end, int lane)
+                                            float *rec, const int32_t *tau_l, int mn,
+                                            const float *err_l, int S, int c, int c_end, int lane)
 {
     while (c < c_end) {
         const int n = c_end - c;
@@ -151,9 +474,9 @@ __device__ __forceinline__ void fill_chunks(const float *prev, float *cur, uint8
         const int r = (n + groups - 1) / groups;
         const int t0 = c * kWave;
         switch (r) {
-#define SPDY_CASE(RR)                                                                 \
-    case RR:                                                                          \
-        fill_group<RR>(prev, cur, choice, tau_l, err_l, S, t0, lane);                 \
+#define SPDY_CASE(RR)                                                                          \
+    case RR:                                                                                   \
+        fill_group<RR, kLevel, kRecord>(prev, cur, choice, rec, tau_l, mn, err_l, S, t0, lane); \
         break;
             SPDY_CASE(1)
             SPDY_CASE(2)
@@ -180,15 +503,15 @@ __device__ __forceinline__ void argmin_merge(float &bv, int &bt, float v, int t)
     }
 }
 
-// Smallest t <= B attaining min_t row[t], reduced over the workgroup.  scratch_v / scratch_t: one
-// word per wave each, in LDS, not aliasing row.  Result valid in thread 0.
-__device__ __forceinline__ void block_argmin(const float *row, int B, float *scratch_v,
+// Smallest t <= top attaining min_t row[t], reduced over the workgroup.  scratch_v / scratch_t:
+// one word per wave each, in LDS, not aliasing row.  Result valid in thread 0.
+__device__ __forceinline__ void block_argmin(const float *row, int top, float *scratch_v,
                                              int *scratch_t, float &out_v, int &out_t)
 {
     const int tid = threadIdx.x, nthreads = blockDim.x;
     float bv = __builtin_inff();
     int bt = INT32_MAX;
-    for (int t = tid; t <= B; t += nthreads)
+    for (int t = tid; t <= top; t += nthreads)
         argmin_merge(bv, bt, row[t], t);
 #pragma unroll
     for (int off = kWave / 2; off > 0; off >>= 1) {
@@ -210,101 +533,203 @@ __device__ __forceinline__ void block_argmin(const float *row, int B, float *scr
     }
 }
 
+__device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *tstar, float *cost)
+{
+    cost[k] = bv;
+    tstar[k] = (bv < __builtin_inff()) ? bt : -1;   // -1: no profile meets the budget
+}
+
 // ---------------------------------------------------------------------------------------------
-// Resident path: one workgroup per candidate, both D rows in LDS for all L layers.
+// Resident path: both reduced D rows of a candidate stay in LDS for all L layers.  The waves of a
+// workgroup form `teams` teams of `tw` waves; team i of workgroup b solves candidate
+// b * teams + i.  Barriers are workgroup-wide, so every team steps through the layers together.
+// `pitch` is the record's row pitch; the record row of layer l is l + 1 (D) or l (levels).
+template <bool kLevel>
 __global__ __launch_bounds__(kResidentThreads, 8) void dp_fill_resident(
-    const int32_t *__restrict__ tau, const float *__restrict__ err, int L, int S, int B, int row,
-    uint8_t *__restrict__ choice, int32_t *__restrict__ tstar, float *__restrict__ cost)
+    const LevelPair *__restrict__ pairs, const int32_t *__restrict__ meta, int path, int K, int L,
+    int s8, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
+    int32_t *__restrict__ tstar, float *__restrict__ cost)
 {
     extern __shared__ float lds[];
-    float *row0 = lds;
-    float *row1 = lds + row;
-
-    const int k = blockIdx.x;
+    if (meta[kMetaPath] != path)
+        return;                                  // another launch does the work
+    const int bp = meta[kMetaBudget];
     const int tid = threadIdx.x, nthreads = blockDim.x;
+    if (bp < 0) {                                // even the fastest levels exceed the budget
+        if (tid == 0)
+            write_result(__builtin_inff(), 0, blockIdx.x, tstar, cost);
+        return;
+    }
+    const int teams = meta[kMetaTeams];
+    const int tw = meta[kMetaTeamWaves];
+    if ((long long)blockIdx.x * teams >= K)
+        return;                                  // the first ceil(K / teams) workgroups suffice
+    const int row = meta[kMetaRow];
     const int lane = tid & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
-    const int nwaves = nthreads / kWave;
+    const int team = wave / tw;
+    const int wv = wave - team * tw;             // this wave's index in its team
+    const int k = blockIdx.x * teams + team;
+    const bool active = team < teams && k < K;
+    const int stride = kHalo + row;              // floats per LDS row incl. its apron
+    float *buf0 = lds + (size_t)(team < teams ? team : 0) * 2 * stride + kHalo;
+    float *buf1 = buf0 + stride;
 
     // D before the first layer: time 0 costs nothing, nothing else is reachable (Eq. 3 then is
     // the general update).  -0.0f + e returns e bit for bit for every e, +0.0f would not for
-    // e = -0.0f.
-    for (int t = tid; t < row; t += nthreads)
-        row0[t] = (t == 0) ? -0.0f : __builtin_inff();
+    // e = -0.0f.  Aprons and chunks a layer does not compute keep this +inf.
+    for (int i = tid; i < teams * 2 * stride; i += nthreads)
+        lds[i] = (i % (2 * stride) == kHalo) ? -0.0f : __builtin_inff();
     __syncthreads();
 
-    const int nchunks = row / kWave;
-    const int c_begin = (int)((long long)wave * nchunks / nwaves);
-    const int c_end = (int)((long long)(wave + 1) * nchunks / nwaves);
-    const float *err_k = err + (size_t)k * L * S;
-    uint8_t *choice_k = choice + (size_t)k * L * row;
+    const int32_t *nact = meta + kMetaHeader + L;
+    const LevelPair *pairs_k = pairs + (size_t)(active ? k : 0) * L * s8;
 
     for (int l = 0; l < L; ++l) {
-        const float *prev = (l & 1) ? row1 : row0;
-        float *cur = (l & 1) ? row0 : row1;
-        fill_chunks(prev, cur, choice_k + (size_t)l * row, tau + (size_t)l * S,
-                    err_k + (size_t)l * S, S, c_begin, c_end, lane);
+        if (active) {
+            const float *prev = (l & 1) ? buf1 : buf0;
+            float *cur = (l & 1) ? buf0 : buf1;
+            const int n = nact[l];               // chunks of this row that can be finite
+            const int c_begin = (int)((long long)wv * n / tw);
+            const int c_end = (int)((long long)(wv + 1) * n / tw);
+            uint8_t *choice_l = kLevel ? choice + ((size_t)k * L + l) * pitch : nullptr;
+            float *drec_l = kLevel ? nullptr : drec + ((size_t)k * (L + 1) + l + 1) * pitch;
+            fill_chunks_lds<kLevel>(prev, cur, choice_l, drec_l, pairs_k + (size_t)l * s8, s8,
+                                    c_begin, c_end, lane);
+        }
         __syncthreads();
     }
 
-    const float *last = (L & 1) ? row1 : row0;
-    float *scratch = (L & 1) ? row0 : row1;   // the other row is dead now
-    float bv;
-    int bt;
-    block_argmin(last, B, scratch, reinterpret_cast<int *>(scratch) + kResidentThreads / kWave, bv, bt);
-    if (tid == 0) {
-        cost[k] = bv;
-        tstar[k] = (bv < __builtin_inff()) ? bt : -1;   // -1: no profile meets the budget
+    // final argmin over t' <= bp within each team; the other row (and its apron) is dead now
+    const float *last = (L & 1) ? buf1 : buf0;
+    float *scratch_v = ((L & 1) ? buf0 : buf1) - kHalo;
+    int *scratch_t = reinterpret_cast<int *>(scratch_v) + kResidentWaves;
+    float bv = __builtin_inff();
+    int bt = INT32_MAX;
+    if (active)
+        for (int t = wv * kWave + lane; t <= bp; t += tw * kWave)
+            argmin_merge(bv, bt, last[t], t);
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        const float ov = __shfl_down(bv, off, kWave);
+        const int ot = __shfl_down(bt, off, kWave);
+        argmin_merge(bv, bt, ov, ot);
+    }
+    if (active && lane == 0) {
+        scratch_v[wv] = bv;
+        scratch_t[wv] = bt;
+    }
+    __syncthreads();
+    if (active && wv == 0 && lane == 0) {
+        for (int w = 1; w < tw; ++w)
+            argmin_merge(bv, bt, scratch_v[w], scratch_t[w]);
+        write_result(bv, bt, k, tstar, cost);
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Streamed path (two rows exceed LDS): D rows live in global memory, one launch per layer.
-__global__ void dp_init_rows(float *__restrict__ d0, int row, int K)
+// Streamed path (two reduced rows exceed LDS): D rows live in global memory, one launch per
+// layer.  With the D record the rows ARE the record (layer l reads record row l, writes row
+// l + 1); with the level record two rows per candidate ping-pong.
+
+// Level record: both ping-pong rows start at +inf, D before the first layer has -0.0f at t = 0.
+__global__ void dp_init_rows(const int32_t *__restrict__ meta, float *__restrict__ d0,
+                             float *__restrict__ d1, int pitch, int K)
 {
-    const size_t n = (size_t)K * row;
+    if (meta[kMetaPath] != 0)
+        return;
+    const size_t n = (size_t)K * pitch;
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (size_t)gridDim.x * blockDim.x)
-        d0[i] = (i % row == 0) ? -0.0f : __builtin_inff();
+         i += (size_t)gridDim.x * blockDim.x) {
+        d0[i] = (i % pitch == 0) ? -0.0f : __builtin_inff();
+        d1[i] = __builtin_inff();
+    }
 }
 
-__global__ __launch_bounds__(kStreamThreads) void dp_layer_streamed(
-    const int32_t *__restrict__ tau_l, const float *__restrict__ err_l0, int L, int S, int row,
-    const float *__restrict__ dprev, float *__restrict__ dcur, uint8_t *__restrict__ choice_l0)
+// D record: row 0 of every candidate is D before the first layer, as far as layer 0 reads it.
+__global__ void dp_init_record(const int32_t *__restrict__ meta, float *__restrict__ drec,
+                               int pitch, int L, int K)
 {
+    if (meta[kMetaPath] != 0)
+        return;
+    const int n0 = meta[kMetaHeader + L] * kWave;    // buckets layer 0 computes
+    for (int k = blockIdx.x; k < K; k += gridDim.x) {
+        float *r = drec + (size_t)k * (L + 1) * pitch;
+        for (int t = threadIdx.x; t < n0; t += blockDim.x)
+            r[t] = (t == 0) ? -0.0f : __builtin_inff();
+    }
+}
+
+template <bool kLevel>
+__global__ __launch_bounds__(kStreamThreads) void dp_layer_streamed(
+    const int32_t *__restrict__ tau, const float *__restrict__ err,
+    const int32_t *__restrict__ meta, int l, int L, int S, int pitch,
+    uint8_t *__restrict__ choice, float *__restrict__ drec, const float *__restrict__ dprev,
+    float *__restrict__ dcur)
+{
+    if (meta[kMetaPath] != 0)
+        return;
     const int k = blockIdx.x;
     const int lane = threadIdx.x & (kWave - 1);
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int nchunks = row / kWave;
+    const int32_t *nact = meta + kMetaHeader + L;
+    const int n = nact[l];
+    // chunks the next layer may read beyond this layer's reach must hold +inf in the D record
+    const int n_next = kLevel ? n : nact[l + 1 < L ? l + 1 : l];
     const int c = (blockIdx.y * (kStreamThreads / kWave) + wave) * kStreamGroup;
-    if (c >= nchunks)
+    if (c >= n_next)
         return;
-    const int c_end = min(c + kStreamGroup, nchunks);
-    fill_chunks(dprev + (size_t)k * row, dcur + (size_t)k * row,
-                choice_l0 + (size_t)k * L * row, tau_l, err_l0 + (size_t)k * L * S, S, c, c_end,
-                lane);
-}
-
-__global__ __launch_bounds__(kStreamThreads) void dp_final_argmin(
-    const float *__restrict__ dlast, int row, int B, int32_t *__restrict__ tstar,
-    float *__restrict__ cost)
-{
-    __shared__ float sv[kStreamThreads / kWave];
-    __shared__ int st[kStreamThreads / kWave];
-    const int k = blockIdx.x;
-    float bv;
-    int bt;
-    block_argmin(dlast + (size_t)k * row, B, sv, st, bv, bt);
-    if (threadIdx.x == 0) {
-        cost[k] = bv;
-        tstar[k] = (bv < __builtin_inff()) ? bt : -1;   // -1: no profile meets the budget
+    const float *prev;
+    float *cur;
+    uint8_t *choice_l = nullptr;
+    if constexpr (kLevel) {
+        prev = dprev + (size_t)k * pitch;
+        cur = dcur + (size_t)k * pitch;
+        choice_l = choice + ((size_t)k * L + l) * pitch;
+    } else {
+        prev = drec + ((size_t)k * (L + 1) + l) * pitch;
+        cur = drec + ((size_t)k * (L + 1) + l + 1) * pitch;
+    }
+    const int c_fill = min(c + kStreamGroup, n);
+    if (c < c_fill)
+        fill_chunks<kLevel, false>(prev, cur, choice_l, nullptr, tau + (size_t)l * S,
+                                   meta[kMetaHeader + l], err + ((size_t)k * L + l) * S, S, c,
+                                   c_fill, lane);
+    if constexpr (!kLevel) {
+        const int c_inf = min(c + kStreamGroup, n_next);
+        for (int cc = max(c, n); cc < c_inf; ++cc)
+            cur[cc * kWave + lane] = __builtin_inff();
     }
 }
 
+// Final argmin for the streamed path; `stride` separates the candidates' last rows.
+__global__ __launch_bounds__(kStreamThreads) void dp_final_argmin(
+    const int32_t *__restrict__ meta, const float *__restrict__ dlast, size_t stride, int L,
+    int32_t *__restrict__ tstar, float *__restrict__ cost)
+{
+    __shared__ float sv[kStreamThreads / kWave];
+    __shared__ int st[kStreamThreads / kWave];
+    if (meta[kMetaPath] != 0)
+        return;
+    const int k = blockIdx.x;
+    // buckets beyond the last layer's computed chunks are +inf by construction (not stored)
+    const int top = min(meta[kMetaBudget], meta[kMetaHeader + 2 * L - 1] * kWave - 1);
+    float bv;
+    int bt;
+    block_argmin(dlast + (size_t)k * stride, top, sv, st, bv, bt);
+    if (threadIdx.x == 0)
+        write_result(bv, bt, k, tstar, cost);
+}
+
 // ---------------------------------------------------------------------------------------------
-// Walk back (last loop of Alg. 1): one lane per candidate, L dependent one-byte reads.
-__global__ void dp_backtrace(const int32_t *__restrict__ tau, const uint8_t *__restrict__ choice,
-                             const int32_t *__restrict__ tstar, int K, int L, int S, int row, int16_t *__restrict__ profile)
+// Walk back (last loop of Alg. 1).
+
+// Level record: one lane per candidate, L dependent one-byte reads.
+__global__ void dp_backtrace_levels(const int32_t *__restrict__ tau,
+                                    const int32_t *__restrict__ meta,
+                                    const uint8_t *__restrict__ choice,
+                                    const int32_t *__restrict__ tstar, int K, int L, int S,
+                                    int pitch, int16_t *__restrict__ profile)
 {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= K)
@@ -316,32 +741,190 @@ __global__ void dp_backtrace(const int32_t *__restrict__ tau, const uint8_t *__r
             prof[l] = -1;
         return;
     }
-    const uint8_t *choice_k = choice + (size_t)k * L * row;
+    const int32_t *mn = meta + kMetaHeader;
+    const uint8_t *choice_k = choice + (size_t)k * L * pitch;
     for (int l = L - 1; l >= 0; --l) {
-        const int s = choice_k[(size_t)l * row + t];
+        const int s = choice_k[(size_t)l * pitch + t];
         prof[l] = (int16_t)s;
         if (s >= S)          // cannot happen on a filled table; never index tau out of range
             break;
-        t -= tau[(size_t)l * S + s];
+        t -= tau[(size_t)l * S + s] - mn[l];
         if (t < 0)
             break;
     }
 }
 
-int check_common(const Layout &lay, const void *workspace, size_t workspace_bytes)
+// D record: one wave per candidate.  At (l, t) the lanes try the levels in parallel: lane s
+// forms D_{l-1}[t - shift_s] + err[l][s] with the same single fp32 add as the fill and compares
+// it with D_l[t]; the lowest matching level is the one a strict "<" sweep would have kept.
+// The cost is then re-summed over the profile in layer order, which reproduces the sign of a
+// zero exactly as the level-tracking sweep would (min(+0, -0) is order-blind).
+__global__ __launch_bounds__(kStreamThreads) void dp_backtrace_values(
+    const int32_t *__restrict__ tau, const float *__restrict__ err,
+    const int32_t *__restrict__ meta, const float *__restrict__ drec,
+    const int32_t *__restrict__ tstar, int K, int L, int S, int pitch,
+    int16_t *__restrict__ profile, float *__restrict__ cost)
 {
-    if (lay.status != SPDY_DP_OK)
-        return lay.status;
-    if (!workspace)
-        return SPDY_DP_ERR_NULL;
-    if (workspace_bytes < lay.total)
-        return SPDY_DP_ERR_WORKSPACE;
-    return SPDY_DP_OK;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int k = blockIdx.x * (kStreamThreads / kWave) + threadIdx.x / kWave;
+    if (k >= K)
+        return;
+    int16_t *prof = profile + (size_t)k * L;
+    int t = tstar[k];
+    if (t < 0) {
+        for (int l = lane; l < L; l += kWave)
+            prof[l] = -1;
+        return;
+    }
+    const int32_t *mn = meta + kMetaHeader;
+    const int32_t *nact = meta + kMetaHeader + L;
+    const float *drec_k = drec + (size_t)k * (L + 1) * pitch;
+    const float *err_k = err + (size_t)k * L * S;
+    float target = drec_k[(size_t)L * pitch + t];
+    bool ok = true;
+    for (int l = L - 1; l >= 0; --l) {
+        const int m = mn[l];
+        const int reach = l > 0 ? nact[l - 1] * kWave : 1;   // computed buckets of row l - 1
+        const float *prow = drec_k + (size_t)l * pitch;      // record row l = layer l - 1
+        int found = -1, next_t = 0;
+        float next_target = 0.0f;
+        for (int s0 = 0; s0 < S && found < 0; s0 += kWave) {
+            const int s = s0 + lane;
+            bool match = false;
+            int u = 0;
+            float pv = __builtin_inff();
+            if (s < S) {
+                const long long uu = (long long)t - ((long long)tau[(size_t)l * S + s] - m);
+                if (uu >= 0 && uu < reach) {
+                    u = (int)uu;
+                    pv = l > 0 ? prow[u] : -0.0f;
+                    const float v = pv + err_k[(size_t)l * S + s];
+                    match = v == target;
+                }
+            }
+            const unsigned long long mask = __ballot(match);
+            if (mask) {
+                const int first = __builtin_ctzll(mask);
+                found = s0 + first;
+                next_t = __shfl(u, first, kWave);
+                next_target = __shfl(pv, first, kWave);
+            }
+        }
+        if (found < 0) {     // cannot happen on a filled record
+            ok = false;
+            break;
+        }
+        if (lane == 0)
+            prof[l] = (int16_t)found;
+        t = next_t;
+        target = next_target;
+    }
+    if (!ok) {
+        for (int l = lane; l < L; l += kWave)
+            prof[l] = -2;
+        if (lane == 0)
+            cost[k] = __builtin_nanf("");
+        return;
+    }
+    // lane 0 wrote the profile; make it visible to its own reads, then re-sum in layer order
+    __threadfence();
+    if (lane == 0) {
+        float acc = -0.0f;
+        for (int l = 0; l < L; ++l)
+            acc += err_k[(size_t)l * S + prof[l]];
+        cost[k] = acc;
+    }
 }
 
 int launch_status()
 {
     return hipGetLastError() == hipSuccess ? SPDY_DP_OK : SPDY_DP_ERR_LAUNCH;
+}
+
+template <bool kLevel>
+int launch_fill(const Layout &lay, const int32_t *tau, const float *err, int K, int L, int S,
+                int B, float *cost, char *ws, hipStream_t q)
+{
+    int32_t *meta = reinterpret_cast<int32_t *>(ws + lay.meta_off);
+    int32_t *tstar = reinterpret_cast<int32_t *>(ws + lay.tstar_off);
+    uint8_t *choice = kLevel ? reinterpret_cast<uint8_t *>(ws + lay.record_off) : nullptr;
+    float *drec = kLevel ? nullptr : reinterpret_cast<float *>(ws + lay.record_off);
+    const int pitch = (int)lay.row;
+    const int nchunks = pitch / kWave;
+    const int chunks_per_block = (kStreamThreads / kWave) * kStreamGroup;
+    const int yblocks = (nchunks + chunks_per_block - 1) / chunks_per_block;
+    if (lay.may_stream && yblocks > 65535)
+        return SPDY_DP_ERR_OVERFLOW;
+
+    // The reduced row length is only known on the device, so the resident kernel is enqueued
+    // with an LDS allocation that lets two workgroups share a compute unit and, if the full
+    // budget could need more, once more with a larger one; the prepare kernel picks the launch
+    // that fits and the other returns at once.
+    const size_t full_need = 2 * (lay.row + kHalo) * sizeof(float);
+    int lds_small, lds_large;
+    if (full_need <= (size_t)kLdsHalf) {
+        lds_small = (int)full_need;
+        lds_large = 0;
+    } else {
+        lds_small = kLdsHalf;
+        lds_large = full_need <= (size_t)kLdsBytes ? (int)full_need : kLdsBytes;
+    }
+    auto resident = dp_fill_resident<kLevel>;
+    const int lds_max = lds_large ? lds_large : lds_small;
+    if (lds_max > 64 * 1024 &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(resident),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_max) != hipSuccess)
+        return SPDY_DP_ERR_LAUNCH;
+    const int waves = nchunks < kResidentWaves ? nchunks : kResidentWaves;
+    uint8_t *order = reinterpret_cast<uint8_t *>(ws + lay.order_off);
+    LevelPair *pairs = reinterpret_cast<LevelPair *>(ws + lay.pairs_off);
+    const int s8 = (int)lay.s8;
+
+    hipLaunchKernelGGL(dp_prepare, dim3(1), dim3(256), 0, q, tau, L, S, B, waves, lds_small,
+                       lds_large, meta);
+    hipLaunchKernelGGL(dp_order_levels, dim3(L), dim3(256), 0, q, tau, S, kLevel ? 0 : 1, order);
+    const size_t n_pairs = (size_t)K * L * lay.s8;
+    const size_t stage_blocks = (n_pairs + 255) / 256;
+    hipLaunchKernelGGL(dp_stage_levels, dim3((unsigned)(stage_blocks < 65536 ? stage_blocks : 65536)),
+                       dim3(256), 0, q, tau, err, meta, order, K, L, S, s8, pairs);
+    hipLaunchKernelGGL(resident, dim3(K), dim3(waves * kWave), lds_small, q, pairs, meta, 1, K, L,
+                       s8, pitch, choice, drec, tstar, cost);
+    if (lds_large)
+        hipLaunchKernelGGL(resident, dim3(K), dim3(waves * kWave), lds_large, q, pairs, meta, 2, K,
+                           L, s8, pitch, choice, drec, tstar, cost);
+    if (!lay.may_stream)
+        return launch_status();
+
+    // the reduced rows may still exceed LDS: enqueue the per-layer path as well; each kernel
+    // looks at the prepare kernel's verdict and exactly one of the two paths does the work
+    float *d0 = nullptr, *d1 = nullptr;
+    if constexpr (kLevel) {
+        d0 = reinterpret_cast<float *>(ws + lay.rows_off);
+        d1 = d0 + (size_t)K * lay.row;
+        hipLaunchKernelGGL(dp_init_rows, dim3(1024), dim3(256), 0, q, meta, d0, d1, pitch, K);
+    } else {
+        hipLaunchKernelGGL(dp_init_record, dim3(K < 4096 ? K : 4096), dim3(256), 0, q, meta, drec,
+                           pitch, L, K);
+    }
+    const dim3 grid(K, yblocks);
+    auto layer = dp_layer_streamed<kLevel>;
+    for (int l = 0; l < L; ++l)
+        hipLaunchKernelGGL(layer, grid, dim3(kStreamThreads), 0, q, tau, err, meta, l, L, S, pitch,
+                           choice, drec, (l & 1) ? d1 : d0, (l & 1) ? d0 : d1);
+    const float *dlast = kLevel ? ((L & 1) ? d1 : d0) : drec + (size_t)L * pitch;
+    const size_t stride = kLevel ? (size_t)pitch : ((size_t)L + 1) * pitch;
+    hipLaunchKernelGGL(dp_final_argmin, dim3(K), dim3(kStreamThreads), 0, q, meta, dlast, stride,
+                       L, tstar, cost);
+    return launch_status();
+}
+
+int validate(const Layout &lay, const void *workspace)
+{
+    if (lay.status != SPDY_DP_OK)
+        return lay.status;
+    if (!workspace)
+        return SPDY_DP_ERR_NULL;
+    return SPDY_DP_OK;
 }
 
 }  // namespace
@@ -350,21 +933,29 @@ extern "C" {
 
 size_t spdy_dp_workspace_bytes(int K, int L, int S, int B)
 {
-    const Layout lay = make_layout(K, L, S, B);
-    return lay.status == SPDY_DP_OK ? lay.total : 0;
+    const Layout lay = make_layout(K, L, S, B, SIZE_MAX);
+    return lay.status == SPDY_DP_OK ? lay.total_value : 0;
 }
 
-int spdy_dp_workspace_layout(int K, int L, int S, int B, size_t *choice_offset,
-                             size_t *choice_pitch, size_t *tstar_offset)
+size_t spdy_dp_workspace_bytes_min(int K, int L, int S, int B)
 {
-    if (!choice_offset || !choice_pitch || !tstar_offset)
+    const Layout lay = make_layout(K, L, S, B, SIZE_MAX);
+    return lay.status == SPDY_DP_OK ? lay.total_level : 0;
+}
+
+int spdy_dp_workspace_layout(int K, int L, int S, int B, size_t workspace_bytes, size_t out[6])
+{
+    if (!out)
         return SPDY_DP_ERR_NULL;
-    const Layout lay = make_layout(K, L, S, B);
+    const Layout lay = make_layout(K, L, S, B, workspace_bytes);
     if (lay.status != SPDY_DP_OK)
         return lay.status;
-    *choice_offset = lay.choice_off;
-    *choice_pitch = lay.row;
-    *tstar_offset = lay.tstar_off;
+    out[0] = (size_t)lay.variant;
+    out[1] = lay.meta_off;
+    out[2] = lay.tstar_off;
+    out[3] = lay.record_off;
+    out[4] = lay.row;
+    out[5] = lay.variant == kValueRecord ? (size_t)L + 1 : (size_t)L;
     return SPDY_DP_OK;
 }
 
@@ -373,64 +964,44 @@ int spdy_dp_fill(const int32_t *tau, const float *err, int K, int L, int S, int 
 {
     if (!tau || !err || !cost)
         return SPDY_DP_ERR_NULL;
-    const Layout lay = make_layout(K, L, S, B);
-    const int st = check_common(lay, workspace, workspace_bytes);
+    const Layout lay = make_layout(K, L, S, B, workspace_bytes);
+    const int st = validate(lay, workspace);
     if (st != SPDY_DP_OK)
         return st;
     hipStream_t q = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
-    uint8_t *choice = reinterpret_cast<uint8_t *>(ws + lay.choice_off);
-    int32_t *tstar = reinterpret_cast<int32_t *>(ws + lay.tstar_off);
-    const int row = (int)lay.row;
-    const int nchunks = row / kWave;
     (void)hipGetLastError();
-
-    if (lay.resident) {
-        const size_t lds = 2 * lay.row * sizeof(float);
-        if (lds > 64 * 1024 &&
-            hipFuncSetAttribute(reinterpret_cast<const void *>(dp_fill_resident),
-                                hipFuncAttributeMaxDynamicSharedMemorySize,
-                                (int)lds) != hipSuccess)
-            return SPDY_DP_ERR_LAUNCH;
-        const int waves = nchunks < kResidentThreads / kWave ? nchunks : kResidentThreads / kWave;
-        hipLaunchKernelGGL(dp_fill_resident, dim3(K), dim3(waves * kWave), lds, q, tau, err, L, S,
-                           B, row, choice, tstar, cost);
-        return launch_status();
-    }
-
-    float *d0 = reinterpret_cast<float *>(ws + lay.drows_off);
-    float *d1 = d0 + (size_t)K * lay.row;
-    hipLaunchKernelGGL(dp_init_rows, dim3(1024), dim3(256), 0, q, d0, row, K);
-    const int chunks_per_block = (kStreamThreads / kWave) * kStreamGroup;
-    const dim3 grid(K, (nchunks + chunks_per_block - 1) / chunks_per_block);
-    for (int l = 0; l < L; ++l) {
-        const float *prev = (l & 1) ? d1 : d0;
-        float *cur = (l & 1) ? d0 : d1;
-        hipLaunchKernelGGL(dp_layer_streamed, grid, dim3(kStreamThreads), 0, q,
-                           tau + (size_t)l * S, err + (size_t)l * S, L, S, row, prev, cur,
-                           choice + (size_t)l * lay.row);
-    }
-    hipLaunchKernelGGL(dp_final_argmin, dim3(K), dim3(kStreamThreads), 0, q,
-                       (L & 1) ? d1 : d0, row, B, tstar, cost);
-    return launch_status();
+    return lay.variant == kLevelRecord
+               ? launch_fill<true>(lay, tau, err, K, L, S, B, cost, ws, q)
+               : launch_fill<false>(lay, tau, err, K, L, S, B, cost, ws, q);
 }
 
-int spdy_dp_backtrace(const int32_t *tau, int K, int L, int S, int B, int16_t *profile,
-                      const void *workspace, size_t workspace_bytes, void *stream)
+int spdy_dp_backtrace(const int32_t *tau, const float *err, int K, int L, int S, int B,
+                      int16_t *profile, float *cost, const void *workspace,
+                      size_t workspace_bytes, void *stream)
 {
-    if (!tau || !profile)
+    if (!tau || !err || !profile || !cost)
         return SPDY_DP_ERR_NULL;
-    const Layout lay = make_layout(K, L, S, B);
-    const int st = check_common(lay, workspace, workspace_bytes);
+    const Layout lay = make_layout(K, L, S, B, workspace_bytes);
+    const int st = validate(lay, workspace);
     if (st != SPDY_DP_OK)
         return st;
     hipStream_t q = static_cast<hipStream_t>(stream);
     const char *ws = static_cast<const char *>(workspace);
-    const uint8_t *choice = reinterpret_cast<const uint8_t *>(ws + lay.choice_off);
+    const int32_t *meta = reinterpret_cast<const int32_t *>(ws + lay.meta_off);
     const int32_t *tstar = reinterpret_cast<const int32_t *>(ws + lay.tstar_off);
     (void)hipGetLastError();
-    hipLaunchKernelGGL(dp_backtrace, dim3((K + kWave - 1) / kWave), dim3(kWave), 0, q, tau,
-                       choice, tstar, K, L, S, (int)lay.row, profile);
+    if (lay.variant == kLevelRecord) {
+        hipLaunchKernelGGL(dp_backtrace_levels, dim3((K + kWave - 1) / kWave), dim3(kWave), 0, q,
+                           tau, meta, reinterpret_cast<const uint8_t *>(ws + lay.record_off),
+                           tstar, K, L, S, (int)lay.row, profile);
+    } else {
+        const int per_block = kStreamThreads / kWave;
+        hipLaunchKernelGGL(dp_backtrace_values, dim3((K + per_block - 1) / per_block),
+                           dim3(kStreamThreads), 0, q, tau, err, meta,
+                           reinterpret_cast<const float *>(ws + lay.record_off), tstar, K, L, S,
+                           (int)lay.row, profile, cost);
+    }
     return launch_status();
 }
 
@@ -440,10 +1011,11 @@ int spdy_dp_solve_batched(const int32_t *tau, const float *err, int K, int L, in
 {
     if (!tau || !err || !profile || !cost)
         return SPDY_DP_ERR_NULL;
-    int st = spdy_dp_fill(tau, err, K, L, S, B, cost, workspace, workspace_bytes, stream);
+    const int st = spdy_dp_fill(tau, err, K, L, S, B, cost, workspace, workspace_bytes, stream);
     if (st != SPDY_DP_OK)
         return st;
-    return spdy_dp_backtrace(tau, K, L, S, B, profile, workspace, workspace_bytes, stream);
+    return spdy_dp_backtrace(tau, err, K, L, S, B, profile, cost, workspace, workspace_bytes,
+                             stream);
 }
 
 const char *spdy_dp_strerror(int status)
@@ -452,8 +1024,8 @@ const char *spdy_dp_strerror(int status)
     case SPDY_DP_OK: return "ok";
     case SPDY_DP_ERR_NULL: return "a required pointer is NULL";
     case SPDY_DP_ERR_DIM: return "K, L and S must be positive and B non-negative";
-    case SPDY_DP_ERR_LEVELS: return "S exceeds 255 levels (one byte per recorded level)";
-    case SPDY_DP_ERR_WORKSPACE: return "workspace smaller than spdy_dp_workspace_bytes()";
+    case SPDY_DP_ERR_LEVELS: return "S exceeds 255 levels (a recorded level is one byte)";
+    case SPDY_DP_ERR_WORKSPACE: return "workspace smaller than spdy_dp_workspace_bytes_min()";
     case SPDY_DP_ERR_OVERFLOW: return "problem size overflows the index arithmetic";
     case SPDY_DP_ERR_LAUNCH: return "HIP runtime refused a kernel launch";
     default: return "unknown status";

@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_function(binding):
     names = declared_functions()
-    assert len(names) >= 6
+    assert len(names) >= 7
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -51,24 +51,35 @@ def test_status_codes_match_header(binding):
 
 
 def test_workspace_size(binding):
-    # one byte per (k, l, t) with rows padded to 64 buckets, plus t* per candidate
     K, L, S, B = 1024, 54, 40, 10000
     row = (B + 1 + 63) // 64 * 64
-    n = binding.spdy_dp_workspace_bytes(K, L, S, B)
-    assert K * L * row + 4 * K <= n <= K * L * row + 4 * K + 1024
-    off, pitch, toff = binding.spdy_dp_workspace_layout(K, L, S, B)
-    assert off == 0 and pitch == row and toff >= K * L * row and toff % 256 == 0
-    # rows that do not fit LDS add two fp32 rows per candidate
+    fast = binding.spdy_dp_workspace_bytes(K, L, S, B)
+    small = binding.spdy_dp_workspace_bytes_min(K, L, S, B)
+    # fp32 D per cell (one extra row per candidate) vs one byte per cell, rows padded to 64
+    staged = 8 * K * L * ((S + 7) // 8 * 8) + L * S     # (shift, err) pairs and visiting order
+    assert 4 * K * (L + 1) * row + staged <= fast <= 4 * K * (L + 1) * row + staged + 16384
+    assert K * L * row + staged <= small <= K * L * row + staged + 16384
+    lay = binding.spdy_dp_workspace_layout(K, L, S, B, fast)
+    assert lay["variant"] == 0 and lay["record_pitch"] == row and lay["record_rows"] == L + 1
+    lay = binding.spdy_dp_workspace_layout(K, L, S, B, fast - 1)
+    assert lay["variant"] == 1 and lay["record_pitch"] == row and lay["record_rows"] == L
+    assert lay["record_offset"] % 256 == 0 and lay["tstar_offset"] % 256 == 0
+    assert lay["tstar_offset"] >= 4 * (8 + 2 * L)
+    assert lay["record_offset"] >= lay["tstar_offset"] + 4 * K + staged
+    with pytest.raises(binding.SpdyDpError) as e:
+        binding.spdy_dp_workspace_layout(K, L, S, B, small - 1)
+    assert e.value.status == binding.ERR_WORKSPACE
+    # rows that do not fit LDS add two fp32 rows per candidate to the level-record variant
     K, L, S, B = 256, 200, 64, 65536
     row = (B + 1 + 63) // 64 * 64
-    n = binding.spdy_dp_workspace_bytes(K, L, S, B)
-    assert n >= K * L * row + 2 * K * row * 4
+    assert binding.spdy_dp_workspace_bytes_min(K, L, S, B) >= K * L * row + 2 * K * row * 4
     # invalid sizes -> 0
-    assert binding.spdy_dp_workspace_bytes(0, 1, 1, 1) == 0
-    assert binding.spdy_dp_workspace_bytes(1, 1, 1, -1) == 0
-    assert binding.spdy_dp_workspace_bytes(1, 1, 256, 1) == 0
-    assert binding.spdy_dp_workspace_bytes(1, 1, 255, 1) > 0
-    assert binding.spdy_dp_workspace_bytes(2 ** 31 - 1, 2 ** 31 - 1, 255, 2 ** 31 - 2000) == 0
+    for f in (binding.spdy_dp_workspace_bytes, binding.spdy_dp_workspace_bytes_min):
+        assert f(0, 1, 1, 1) == 0
+        assert f(1, 1, 1, -1) == 0
+        assert f(1, 1, 256, 1) == 0
+        assert f(1, 1, 255, 1) > 0
+        assert f(2 ** 31 - 1, 2 ** 31 - 1, 255, 2 ** 31 - 2000) == 0
 
 
 def test_argument_errors_are_reported_before_any_launch(binding):
@@ -89,8 +100,11 @@ def test_argument_errors_are_reported_before_any_launch(binding):
     assert solve(fake, fake, 2 ** 31 - 1, 2 ** 31 - 1, 2, 2 ** 31 - 2000, fake, fake, fake,
                  1 << 20, None) == binding.ERR_OVERFLOW
     assert lib.spdy_dp_fill(fake, fake, 1, 1, 1, 1, None, fake, 1 << 20, None) == binding.ERR_NULL
-    assert lib.spdy_dp_backtrace(fake, 1, 1, 1, 1, None, fake, 1 << 20, None) == binding.ERR_NULL
-    assert lib.spdy_dp_backtrace(fake, 1, 1, 1, 1, fake, fake, 8, None) == binding.ERR_WORKSPACE
+    bt = lib.spdy_dp_backtrace
+    assert bt(fake, fake, 1, 1, 1, 1, None, fake, fake, 1 << 20, None) == binding.ERR_NULL
+    assert bt(fake, None, 1, 1, 1, 1, fake, fake, fake, 1 << 20, None) == binding.ERR_NULL
+    assert bt(fake, fake, 1, 1, 1, 1, fake, None, fake, 1 << 20, None) == binding.ERR_NULL
+    assert bt(fake, fake, 1, 1, 1, 1, fake, fake, fake, 8, None) == binding.ERR_WORKSPACE
 
 
 def test_binding_refuses_cpu_tensors(binding):

@@ -22,13 +22,26 @@ def dp():
     return m
 
 
-def gpu_solve(dp, tau, err, B, stream=None):
+@pytest.fixture(scope="module")
+def reference():
+    cache = {}
+
+    def get(name, tau, err, B):
+        if name not in cache:
+            print(f"[parity] {name}: running the oracle on {CPU_THREADS} threads", flush=True)
+            cache[name] = oracle.solve_ref(tau, err, B, threads=CPU_THREADS)
+        return cache[name]
+    return get
+
+
+def gpu_solve(dp, tau, err, B, compact=False, stream=None):
     dev = torch.device("cuda:0")
     tau_d = torch.from_numpy(tau).to(dev)
     err_d = torch.from_numpy(err).to(dev)
     K, L, S = err.shape
-    ws = dp.alloc_workspace(K, L, S, B, dev)
-    ws.fill_(0xAB)   # stale contents must not matter
+    ws = dp.alloc_workspace(K, L, S, B, dev, compact=compact)
+    if ws.numel() < 2 ** 31:
+        ws.fill_(0xAB)   # stale contents must not matter
     profile = torch.full((K, L), -7, dtype=torch.int16, device=dev)
     cost = torch.full((K,), -7.0, dtype=torch.float32, device=dev)
     dp.spdy_dp_solve_batched(tau_d, err_d, B, profile, cost, ws, stream=stream)
@@ -45,30 +58,62 @@ def assert_same(p_gpu, c_gpu, p_ref, c_ref, what):
 
 
 def check_tables(dp, tau, err_k, B, ws, k, K):
-    """Level record and t* of candidate k against the oracle's P where its D is finite."""
+    """The record of candidate k against the oracle's matrices.  The device works on reduced
+    times t' = t - (m_0 + .. + m_l) with m_l = min_s tau[l][s] and computes only chunks that can
+    be finite; every computed cell must equal the oracle's D (value record) or P (level record,
+    where D is finite), every cell it skips must be +inf in the oracle, and t* must agree."""
     L, S = tau.shape
     D, P, prof, cost = oracle.tables_ref(tau, err_k, B)
-    off, pitch, toff = dp.spdy_dp_workspace_layout(K, L, S, B)
-    wsb = ws.cpu().numpy()
-    rec = wsb[off + k * L * pitch: off + (k + 1) * L * pitch].reshape(L, pitch)[:, :B + 1]
-    finite = np.isfinite(D)
-    assert (rec[finite] == P[finite].astype(np.uint8)).all()
-    tstar = wsb[toff:toff + 4 * K].view(np.int32)[k]
+    lay = dp.spdy_dp_workspace_layout(K, L, S, B, ws.numel())
+    meta = ws[lay["meta_offset"]:lay["meta_offset"] + 4 * (8 + 2 * L)].cpu().numpy().view(np.int32)
+    mn = tau.min(axis=1).astype(np.int64)
+    M = int(mn.sum())
+    tstar = ws[lay["tstar_offset"] + 4 * k:lay["tstar_offset"] + 4 * k + 4].cpu().numpy() \
+        .view(np.int32)[0]
+    if M > B:
+        assert meta[0] == -1 and tstar == -1 and np.isinf(cost)
+        return
+    bp = B - M
+    assert meta[0] == bp and meta[1] == M and meta[2] == (bp + 64) // 64 * 64
+    assert (meta[8:8 + L] == mn).all()
+    nact = meta[8 + L:8 + 2 * L].astype(np.int64)
+    lo = np.cumsum(mn)
+    pitch, rows = lay["record_pitch"], lay["record_rows"]
+    esize = 4 if lay["variant"] == 0 else 1
+    a = lay["record_offset"] + k * rows * pitch * esize
+    rec = ws[a:a + rows * pitch * esize].cpu().numpy()
+    rec = rec.view(np.float32 if esize == 4 else np.uint8).reshape(rows, pitch)
+    if meta[3] == 0:     # per-layer kernels ran: two reduced rows (plus aprons) exceed LDS
+        assert 2 * (meta[2] + 640) * 4 > 160 * 1024
+    for l in range(L):
+        n = int(min(nact[l] * 64, bp + 1))
+        want_D = D[l, lo[l]:lo[l] + n]
+        assert np.isinf(D[l, lo[l] + n:lo[l] + bp + 1]).all(), f"layer {l}: reach bound wrong"
+        if lay["variant"] == 0:
+            got = rec[l + 1, :n]
+            assert (got == want_D).all(), f"layer {l}: D record differs"
+        else:
+            fin = np.isfinite(want_D)
+            got = rec[l, :n]
+            assert (got[fin] == P[l, lo[l]:lo[l] + n][fin].astype(np.uint8)).all(), \
+                f"layer {l}: level record differs"
     if np.isfinite(cost):
-        assert tstar == int(np.argmin(D[L - 1]))
+        assert tstar + M == int(np.argmin(D[L - 1]))
     else:
         assert tstar == -1
 
 
 # --------------------------------------------------------------------------- the five configs
+@pytest.mark.parametrize("compact", [False, True], ids=["d_record", "level_record"])
 @pytest.mark.parametrize("name", ["tiny", "rn50_k1", "rn50_k1024", "bert_k4096", "stress_k256"])
-def test_config_bit_exact(dp, name):
+def test_config_bit_exact(dp, name, compact, reference):
     cfg = workloads.CONFIGS[name]
-    print(f"[parity] config {name}: K={cfg.K} L={cfg.L} S={cfg.S} B={cfg.B}", flush=True)
+    print(f"[parity] config {name}: K={cfg.K} L={cfg.L} S={cfg.S} B={cfg.B} "
+          f"compact={compact}", flush=True)
     tau, err, B = workloads.generate(cfg)
-    p_gpu, c_gpu, ws = gpu_solve(dp, tau, err, B)
-    print(f"[parity] {name}: gpu done, running oracle on {CPU_THREADS} threads", flush=True)
-    p_ref, c_ref = oracle.solve_ref(tau, err, B, threads=CPU_THREADS)
+    p_gpu, c_gpu, ws = gpu_solve(dp, tau, err, B, compact=compact)
+    print(f"[parity] {name}: gpu done", flush=True)
+    p_ref, c_ref = reference(name, tau, err, B)
     assert_same(p_gpu, c_gpu, p_ref, c_ref, name)
     assert np.isfinite(c_ref).all()
     # properties that hold at any size: budget met; cost is the layer-order fp32 sum
@@ -80,9 +125,8 @@ def test_config_bit_exact(dp, name):
     for l in range(1, cfg.L):
         acc = (acc + e[:, l]).astype(np.float32)
     assert (acc.view(np.uint32) == c_gpu.view(np.uint32)).all()
-    if cfg.K * cfg.L * (cfg.B + 1) < 2e9:
-        for k in sorted({0, cfg.K // 2, cfg.K - 1}):
-            check_tables(dp, tau, err[k], B, ws, k, cfg.K)
+    for k in sorted({0, cfg.K // 2, cfg.K - 1}):
+        check_tables(dp, tau, err[k], B, ws, k, cfg.K)
 
 
 # --------------------------------------------------------------------------- shapes and edges
@@ -100,7 +144,7 @@ def test_random_tables_bit_exact(dp, shape):
     K, L, S, B = shape
     print(f"[parity] random tables K={K} L={L} S={S} B={B}", flush=True)
     rng = np.random.default_rng(K * 1000003 + L * 10007 + S * 101 + B)
-    for variant in range(4):
+    for variant in range(5):
         kw = dict(tau_max=max(1, B // max(1, L // 2)))
         if variant == 1:
             kw.update(integer_err=3)                        # ties everywhere
@@ -108,11 +152,14 @@ def test_random_tables_bit_exact(dp, shape):
             kw.update(zero_tau_frac=0.2, over_budget_frac=0.2, inf_err_frac=0.1)
         elif variant == 3:
             kw.update(integer_err=2, zero_tau_frac=0.3, tau_max=max(1, B // (2 * L) + 1))
+        elif variant == 4:   # large per-layer floors: the reduced budget is a fraction of B
+            kw.update(integer_err=4, tau_max=max(1, B // (2 * L)), layer_floor=B // L)
         tau, err, _ = workloads.random_instance(rng, K, L, S, B, **kw)
-        p_gpu, c_gpu, ws = gpu_solve(dp, tau, err, B)
         p_ref, c_ref = oracle.solve_ref(tau, err, B)
-        assert_same(p_gpu, c_gpu, p_ref, c_ref, f"{shape} variant {variant}")
-        check_tables(dp, tau, err[K - 1], B, ws, K - 1, K)
+        for compact in (False, True):
+            p_gpu, c_gpu, ws = gpu_solve(dp, tau, err, B, compact=compact)
+            assert_same(p_gpu, c_gpu, p_ref, c_ref, f"{shape} variant {variant} compact={compact}")
+            check_tables(dp, tau, err[K - 1], B, ws, K - 1, K)
 
 
 def test_infeasible_and_mixed_batches(dp):
@@ -121,10 +168,11 @@ def test_infeasible_and_mixed_batches(dp):
     err = np.array([[[0, 1, 2], [0, 1, 2], [0, 1, 2]],
                     [[0, 1, 2], [0, 1, 2], [np.inf, np.inf, np.inf]]], dtype=np.float32)
     for B in (0, 3, 4, 9, 15, 200):
-        p_gpu, c_gpu, _ = gpu_solve(dp, tau, err, B)
         p_ref, c_ref = oracle.solve_ref(tau, err, B)
-        assert_same(p_gpu, c_gpu, p_ref, c_ref, f"B={B}")
-        assert np.isinf(c_gpu[1]) and (p_gpu[1] == -1).all()
+        for compact in (False, True):
+            p_gpu, c_gpu, _ = gpu_solve(dp, tau, err, B, compact=compact)
+            assert_same(p_gpu, c_gpu, p_ref, c_ref, f"B={B} compact={compact}")
+            assert np.isinf(c_gpu[1]) and (p_gpu[1] == -1).all()
 
 
 def test_negative_zero_and_subnormal_errors(dp):
@@ -135,9 +183,10 @@ def test_negative_zero_and_subnormal_errors(dp):
                     [[1, -0.0], [-0.0, 0.0], [0.0, -0.0]],
                     [[-1, 2], [3, -2.5], [0.5, -0.0]]], dtype=np.float32)
     for B in (0, 1, 2, 4, 70):
-        p_gpu, c_gpu, _ = gpu_solve(dp, tau, err, B)
         p_ref, c_ref = oracle.solve_ref(tau, err, B)
-        assert_same(p_gpu, c_gpu, p_ref, c_ref, f"B={B}")
+        for compact in (False, True):
+            p_gpu, c_gpu, _ = gpu_solve(dp, tau, err, B, compact=compact)
+            assert_same(p_gpu, c_gpu, p_ref, c_ref, f"B={B} compact={compact}")
 
 
 def test_stages_equal_the_fused_call_and_streams(dp):
@@ -153,7 +202,7 @@ def test_stages_equal_the_fused_call_and_streams(dp):
     side.wait_stream(torch.cuda.current_stream())
     with torch.cuda.stream(side):
         dp.spdy_dp_fill(tau_d, err_d, B, cost, ws)
-        dp.spdy_dp_backtrace(tau_d, K, B, profile, ws)
+        dp.spdy_dp_backtrace(tau_d, err_d, B, profile, cost, ws)
     side.synchronize()
     p_ref, c_ref = oracle.solve_ref(tau, err, B)
     assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, "staged, side stream")

@@ -95,15 +95,19 @@ def generate(cfg: Config, seed: int = 0, K: int | None = None):
 def random_instance(rng: np.random.Generator, K: int, L: int, S: int, B: int, *,
                     tau_max: int | None = None, integer_err: int | None = None,
                     zero_tau_frac: float = 0.0, over_budget_frac: float = 0.0,
-                    inf_err_frac: float = 0.0):
+                    inf_err_frac: float = 0.0, layer_floor: int = 0):
     """Unstructured random tables for tests (no monotonicity in s, Sec. 3.1: timings are
     non-linear and a sparse layer can be slower than the dense one).
 
     ``integer_err=m`` draws errors from {0..m-1} (sums exact in fp32, ties frequent); otherwise
     errors are uniform in [0, 1).  Fractions select entries forced to tau = 0, tau > B, err = +inf.
+    ``layer_floor > 0`` adds a random per-layer offset in [0, layer_floor] to every time of the
+    layer, so that the smallest time of a layer is well above zero.
     """
     tau_max = max(1, B // 2) if tau_max is None else tau_max
     tau = rng.integers(0, tau_max + 1, size=(L, S), dtype=np.int64)
+    if layer_floor > 0:
+        tau += rng.integers(0, layer_floor + 1, size=(L, 1), dtype=np.int64)
     if zero_tau_frac > 0:
         tau[rng.random((L, S)) < zero_tau_frac] = 0
     if over_budget_frac > 0:
