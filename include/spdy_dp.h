@@ -70,12 +70,13 @@ extern "C" {
 #define SPDY_DP_ERR_LAUNCH (-9)    /* the HIP runtime refused a launch (see hipGetLastError)    */
 
 /* Bytes of device workspace for the fast variant (fp32 D recorded per cell), or 0 if the sizes
- * are invalid.  About 4 * K * (L + 1) * (B + 1) bytes. */
+ * are invalid.  About 4 * K * (L + 1) * (B + 1) + 8 * K * L * S bytes. */
 size_t spdy_dp_workspace_bytes(int K, int L, int S, int B);
 
 /* Smallest workspace accepted (one-byte level record per cell), or 0 if the sizes are invalid.
- * About K * L * (B + 1) bytes, plus 8 * K * (B + 1) when two rows of B + 1 floats exceed the
- * 160 KB of LDS of a compute unit.  Any size in between selects this variant too. */
+ * About K * L * (B + 1) + 8 * K * L * S bytes, plus 8 * K * (B + 1) when two rows of B + 1
+ * floats exceed the 160 KB of LDS of a compute unit.  Any size in between selects this variant
+ * too. */
 size_t spdy_dp_workspace_bytes_min(int K, int L, int S, int B);
 
 /* Solve all K candidates: the whole of Alg. 1 (table fill, final argmin over t, walk back).
@@ -105,9 +106,9 @@ int spdy_dp_backtrace(const int32_t *tau, const float *err, int K, int L, int S,
 /* Test/debug accessor: where things are in a workspace of `workspace_bytes` bytes.
  *   out[0] variant: 0 = fp32 D record, 1 = one-byte level record
  *   out[1] byte offset of the int32 header: [0] B - M (or -1 if M > B: nobody is feasible),
- *          [1] M, [2] reduced row length (B - M + 1 padded to 64), [3] 1 if two reduced rows fit
- *          LDS; then m_l at [8 + l] and the number of computed 64-bucket chunks of layer l at
- *          [8 + L + l]
+ *          [1] M, [2] reduced row length (B - M + 1 padded to 64), [3] 0 if the rows live in
+ *          global memory (per-layer kernels), 1 or 2 if they live in LDS; then m_l at [8 + l]
+ *          and the number of computed 64-bucket chunks of layer l at [8 + L + l]
  *   out[2] byte offset of int32 t*[K] (reduced time t* - M, or -1 if infeasible)
  *   out[3] byte offset of the record
  *   out[4] record pitch in elements (buckets per row, a multiple of 64)

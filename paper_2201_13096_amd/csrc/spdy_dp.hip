@@ -36,7 +36,8 @@
 namespace {
 
 constexpr int kWave = 64;            // lanes per wavefront = buckets per chunk
-constexpr int kMaxGroup = 10;        // most chunks a wave keeps in registers at once
+constexpr int kMaxGroup = 13;        // most chunks a wave keeps in registers at once (D record)
+constexpr int kMaxGroupLevel = 10;   // same when the level is tracked too (more registers each)
 constexpr int kResidentThreads = 1024;
 constexpr int kResidentWaves = kResidentThreads / kWave;
 constexpr int kStreamThreads = 256;  // per-layer kernel: 4 waves per workgroup
@@ -51,10 +52,13 @@ constexpr int kMetaHeader = 8;       // int32 words before the per-layer arrays
 
 // kMetaPath: 0 = per-layer kernels, 1 / 2 = LDS-resident kernel launched with the smaller /
 // larger LDS allocation.  kMetaTeamWaves x kMetaTeams <= waves of a resident workgroup.
+// kMetaInPlace: every wave of a team holds all its chunks of a row in registers, so one LDS
+// row per candidate suffices (written back between two barriers); otherwise two rows alternate.
 enum MetaWord {
     kMetaBudget = 0, kMetaMinTime = 1, kMetaRow = 2, kMetaPath = 3, kMetaTeamWaves = 4,
-    kMetaTeams = 5
+    kMetaTeams = 5, kMetaInPlace = 6
 };
+constexpr int kStageCands = 64;      // candidates staged per workgroup of dp_stage_levels
 
 struct LevelPair {   // one level of one layer of one candidate, as the resident kernel reads it
     int32_t shift;   // tau[l][s] - m_l  (INT32_MAX in padding entries)
@@ -73,7 +77,6 @@ struct Layout {
     size_t meta_off;     // int32 meta[kMetaHeader + 2 L]
     size_t tstar_off;    // int32 tstar[K]
     size_t s8;           // levels per layer padded to a multiple of kBatch
-    size_t order_off;    // uint8 order[L][S]: level visited r-th in layer l
     size_t pairs_off;    // LevelPair pairs[K][L][s8]
     size_t record_off;   // float D[K][L+1][row]  or  uint8 P[K][L][row]
     size_t rows_off;     // float D[2][K][row], level record with may_stream only
@@ -111,8 +114,7 @@ Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes)
     lay.s8 = align_up((size_t)S, kBatch);
     lay.meta_off = 0;
     lay.tstar_off = align_up((kMetaHeader + 2 * (size_t)L) * sizeof(int32_t), kAlign);
-    lay.order_off = align_up(lay.tstar_off + (size_t)K * sizeof(int32_t), kAlign);
-    lay.pairs_off = align_up(lay.order_off + (size_t)L * S, kAlign);
+    lay.pairs_off = align_up(lay.tstar_off + (size_t)K * sizeof(int32_t), kAlign);
     lay.record_off =
         align_up(lay.pairs_off + (size_t)K * L * lay.s8 * sizeof(LevelPair), kAlign);
     lay.total_value = lay.record_off + (size_t)K * ((size_t)L + 1) * lay.row * sizeof(float);
@@ -136,59 +138,65 @@ Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes)
 // chunks of each reduced row can hold a finite value (largest reachable reduced time after
 // layer l is sum_{j<=l} max_s (tau[j][s] - m_j) over the levels that fit the reduced budget).
 // It also picks the path: which launch of the resident kernel (LDS allocation lds_small or
-// lds_large bytes, `waves` waves per workgroup) fits, and into how many teams its waves split.
+// lds_large bytes, `waves` waves per workgroup) fits, into how many teams its waves split, and
+// whether one LDS row per candidate is enough.  One workgroup; thread i owns a slice of layers.
 __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ tau, int L, int S,
-                                                  int B, int waves, int lds_small, int lds_large,
-                                                  int32_t *__restrict__ meta)
+                                                  int B, int waves, int max_group, int lds_small,
+                                                  int lds_large, int32_t *__restrict__ meta)
 {
+    __shared__ long long s_sum[256];
     __shared__ int s_budget;
-    const int tid = threadIdx.x, n = blockDim.x;
+    const int tid = threadIdx.x;
     int32_t *mn = meta + kMetaHeader;
     int32_t *nact = meta + kMetaHeader + L;
-    for (int l = tid; l < L; l += n) {
+    const int per = (L + 255) / 256;
+    const int l0 = min(L, tid * per), l1 = min(L, l0 + per);
+
+    long long local = 0;
+    for (int l = l0; l < l1; ++l) {
         int m = INT32_MAX;
         for (int s = 0; s < S; ++s)
             m = min(m, tau[(size_t)l * S + s]);
         mn[l] = m;
+        local += m;
     }
+    s_sum[tid] = local;
     __syncthreads();
     if (tid == 0) {
         long long M = 0;
-        for (int l = 0; l < L; ++l)
-            M += mn[l];
+        for (int i = 0; i < 256; ++i)
+            M += s_sum[i];
         const int bp = (M > B) ? -1 : (int)(B - M);
         const int rowp = bp < 0 ? 0 : (bp + kWave) / kWave * kWave;
         meta[kMetaBudget] = bp;
         meta[kMetaMinTime] = M > INT32_MAX ? INT32_MAX : (int)M;
         meta[kMetaRow] = rowp;
-        const long long team_lds = 2 * ((long long)rowp + kHalo) * (long long)sizeof(float);
-        int path = 0, lds = 0;
-        if (bp < 0 || team_lds <= lds_small) {   // an infeasible table is reported by path 1
-            path = 1;
-            lds = lds_small;
-        } else if (team_lds <= lds_large) {
-            path = 2;
-            lds = lds_large;
-        }
-        // teams: as many candidates per workgroup as keeps about kMaxGroup chunks per wave
-        int teams = 1;
-        if (path != 0 && bp >= 0) {
-            const int want = (rowp / kWave + kMaxGroup - 1) / kMaxGroup;   // waves per candidate
-            teams = waves / (want < 1 ? 1 : want);
-            const long long fit = lds / team_lds;
-            if (teams > fit)
-                teams = (int)fit;
-            if (teams < 1)
-                teams = 1;
+        int path = 1, teams = 1, inplace = 0;     // an infeasible table is reported by path 1
+        if (bp >= 0) {
+            const long long one_row = ((long long)rowp + kHalo) * (long long)sizeof(float);
+            const int want = (rowp / kWave + max_group - 1) / max_group;   // waves per candidate
+            inplace = want <= waves ? 1 : 0;
+            const long long team_lds = inplace ? one_row : 2 * one_row;
+            const int lds = team_lds <= lds_small ? lds_small : lds_large;
+            path = team_lds <= lds_small ? 1 : (team_lds <= lds_large ? 2 : 0);
+            if (path != 0 && inplace) {
+                // as many candidates per workgroup as keeps every wave at <= max_group chunks
+                teams = waves / want;
+                const long long fit = lds / team_lds;
+                if (teams > fit)
+                    teams = (int)fit;
+            }
         }
         meta[kMetaPath] = path;
         meta[kMetaTeams] = teams;
         meta[kMetaTeamWaves] = waves / teams;
+        meta[kMetaInPlace] = inplace;
         s_budget = bp;
     }
     __syncthreads();
     const int bp = s_budget;
-    for (int l = tid; l < L; l += n) {
+    local = 0;
+    for (int l = l0; l < l1; ++l) {
         int span = 0;
         if (bp >= 0) {
             const int m = mn[l];
@@ -199,67 +207,69 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
             }
         }
         nact[l] = span;
+        local += span;
+    }
+    s_sum[tid] = local;
+    __syncthreads();
+    if (tid == 0) {                               // exclusive scan of the slices' sums
+        long long h = 0;
+        for (int i = 0; i < 256; ++i) {
+            const long long v = s_sum[i];
+            s_sum[i] = h;
+            h += v;
+        }
     }
     __syncthreads();
-    if (tid == 0) {
-        long long h = 0;
-        for (int l = 0; l < L; ++l) {
-            h += nact[l];
-            const long long top = h < bp ? h : bp;
-            nact[l] = bp < 0 ? 0 : (int)((top + kWave) / kWave);
-        }
+    long long h = s_sum[tid];
+    for (int l = l0; l < l1; ++l) {
+        h += nact[l];
+        const long long top = h < bp ? h : bp;
+        nact[l] = bp < 0 ? 0 : (int)((top + kWave) / kWave);
     }
 }
 
 // ---------------------------------------------------------------------------------------------
-// Visiting order of the levels of each layer.  When only the minimum is needed (D record) the
-// levels are sorted by shift, ties by index, so the levels a group of buckets can use form a
-// prefix; when the level itself is tracked the order stays ascending in s (ties go to the
-// smallest s through the strict "<").  One workgroup per layer, one thread per level.
-__global__ __launch_bounds__(256) void dp_order_levels(const int32_t *__restrict__ tau, int S,
-                                                       int sorted, uint8_t *__restrict__ order)
-{
-    const int l = blockIdx.x, s = threadIdx.x;
-    if (s >= S)
-        return;
-    int rank = s;
-    if (sorted) {
-        const int32_t *tau_l = tau + (size_t)l * S;
-        const int mine = tau_l[s];
-        rank = 0;
-        for (int o = 0; o < S; ++o) {
-            const int other = tau_l[o];
-            rank += (other < mine || (other == mine && o < s)) ? 1 : 0;
-        }
-    }
-    order[(size_t)l * S + rank] = (uint8_t)s;
-}
-
-// pairs[k][l][r] = (tau[l][s] - m_l, err[k][l][s]) for s = order[l][r]; padding up to s8 is
-// (INT32_MAX, +inf), which no group of buckets can use.
+// Stage the levels for the resident kernel: pairs[k][l][r] = (tau[l][s] - m_l, err[k][l][s])
+// where s is the r-th level in visiting order; padding up to s8 is (INT32_MAX, +inf), which no
+// group of buckets can use.  When only the minimum is needed (D record) the levels are visited
+// by ascending shift, ties by index, so the levels a group of buckets can use form a prefix;
+// when the level itself is tracked the order stays ascending in s (ties go to the smallest s
+// through the strict "<").  Workgroup (l, g) stages layer l for candidates g*64 .. g*64+63.
 __global__ __launch_bounds__(256) void dp_stage_levels(const int32_t *__restrict__ tau,
-                                                       const float *__restrict__ err,
-                                                       const int32_t *__restrict__ meta,
-                                                       const uint8_t *__restrict__ order, int K,
-                                                       int L, int S, int s8,
+                                                       const float *__restrict__ err, int K,
+                                                       int L, int S, int s8, int sorted,
                                                        LevelPair *__restrict__ pairs)
 {
-    const size_t n = (size_t)K * L * s8;
-    const int32_t *mn = meta + kMetaHeader;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (size_t)gridDim.x * blockDim.x) {
-        const int r = (int)(i % s8);
-        const size_t kl = i / s8;
-        const int l = (int)(kl % L);
+    __shared__ int s_shift[256];
+    __shared__ int s_level[256];
+    const int l = blockIdx.x, tid = threadIdx.x;
+    if (tid < S) {
+        const int32_t *tau_l = tau + (size_t)l * S;
+        const int mine = tau_l[tid];
+        int rank = 0, m = INT32_MAX;
+        for (int o = 0; o < S; ++o) {
+            const int other = tau_l[o];
+            m = min(m, other);
+            rank += (other < mine || (other == mine && o < tid)) ? 1 : 0;
+        }
+        if (!sorted)
+            rank = tid;
+        s_shift[rank] = mine - m;
+        s_level[rank] = tid;
+    }
+    __syncthreads();
+    const int k0 = blockIdx.y * kStageCands;
+    const int nk = min(kStageCands, K - k0);
+    for (int i = tid; i < nk * s8; i += blockDim.x) {
+        const int k = k0 + i / s8, r = i % s8;
         LevelPair p;
         p.shift = INT32_MAX;
         p.err = __builtin_inff();
         if (r < S) {
-            const int s = order[(size_t)l * S + r];
-            p.shift = tau[(size_t)l * S + s] - mn[l];
-            p.err = err[kl * S + s];
+            p.shift = s_shift[r];
+            p.err = err[((size_t)k * L + l) * S + s_level[r]];
         }
-        pairs[i] = p;
+        pairs[((size_t)k * L + l) * s8 + r] = p;
     }
 }
 
@@ -274,20 +284,17 @@ __device__ __forceinline__ void vmin3(float &b, float x, float y)
     asm("v_min3_f32 %0, %0, %1, %2" : "+v"(b) : "v"(x), "v"(y));
 }
 
-// Resident path: one group of R chunks (R*64 consecutive reduced buckets from t0) of one layer.
-//   prev / cur : LDS rows, prev[-kHalo .. -1] reads +inf
-//   pairs_l    : the layer's s8 staged levels (64-byte aligned), sorted by shift unless kLevel
-//   order_l    : level index of the r-th staged level (kLevel only: the identity)
+// Resident path: the levels of one layer swept over one group of R chunks (R*64 consecutive
+// reduced buckets from t0); best[j] / arg[j] belong to bucket t0 + 64*j + lane.
+//   prev    : LDS row of the previous layer, prev[-kHalo .. -1] reads +inf
+//   pairs_l : the layer's s8 staged levels (64-byte aligned), sorted by shift unless kLevel
+// A level applies to the group if its shift does not exceed the group's last bucket; lanes
+// left of the shift then read the +inf apron.
 template <int R, bool kLevel>
-__device__ __forceinline__ void fill_group_lds(const float *__restrict__ prev,
-                                               float *__restrict__ cur,
-                                               uint8_t *__restrict__ choice,
-                                               float *__restrict__ rec,
-                                               const LevelPair *__restrict__ pairs_l, int s8,
-                                               int t0, int lane)
+__device__ __forceinline__ void sweep_group(const float *__restrict__ prev,
+                                            const LevelPair *__restrict__ pairs_l, int s8, int t0,
+                                            int lane, float (&best)[R], unsigned (&arg)[R])
 {
-    float best[R];
-    unsigned arg[R];
 #pragma unroll
     for (int j = 0; j < R; ++j) {
         best[j] = __builtin_inff();
@@ -295,10 +302,16 @@ __device__ __forceinline__ void fill_group_lds(const float *__restrict__ prev,
     }
     const int last = t0 + R * kWave - 1;      // last bucket of the group
     const char *pl = reinterpret_cast<const char *>(prev + t0 + lane);
-    const LevelPair *pp =
-        static_cast<const LevelPair *>(__builtin_assume_aligned(pairs_l, kBatch * 8));
+    // the staged levels were written by an earlier kernel: read them through the constant
+    // address space so that the (wave-uniform) fetches become scalar loads
+    typedef const __attribute__((address_space(4))) LevelPair *ConstPairs;
+    const ConstPairs pp = (ConstPairs)(uintptr_t)__builtin_assume_aligned(pairs_l, kBatch * 8);
 
-    auto sweep = [&]() {
+    auto row_at = [&](int shift) {
+        return reinterpret_cast<const float *>(pl - (size_t)((unsigned)shift * 4u));
+    };
+
+    if constexpr (kLevel) {
         for (int s0 = 0; s0 < s8; s0 += kBatch) {
             int ts[kBatch];
             float es[kBatch];
@@ -307,86 +320,140 @@ __device__ __forceinline__ void fill_group_lds(const float *__restrict__ prev,
                 ts[i] = pp[s0 + i].shift;
                 es[i] = pp[s0 + i].err;
             }
-            if constexpr (kLevel) {
 #pragma unroll
-                for (int i = 0; i < kBatch; ++i) {
-                    if (ts[i] > last)
-                        continue;             // every lane would read left of the apron
-                    const float *p =
-                        reinterpret_cast<const float *>(pl - (size_t)((unsigned)ts[i] * 4u));
-                    const unsigned s = (unsigned)(s0 + i);
+            for (int i = 0; i < kBatch; ++i) {
+                // a level whose shift lies beyond the group is moved so that every lane reads
+                // the apron (+inf never wins a strict "<"): no branch, the order in s is kept
+                const float *p = row_at(min(ts[i], last + 1));
+                const unsigned s = (unsigned)(s0 + i);
 #pragma unroll
-                    for (int j = 0; j < R; ++j) {
-                        const float v = p[j * kWave] + es[i];
-                        if (v < best[j]) {
-                            best[j] = v;
-                            arg[j] = s;
-                        }
+                for (int j = 0; j < R; ++j) {
+                    const float v = p[j * kWave] + es[i];
+                    if (v < best[j]) {
+                        best[j] = v;
+                        arg[j] = s;
                     }
-                }
-            } else {
-#pragma unroll
-                for (int i = 0; i < kBatch; i += 2) {
-                    if (ts[i] > last)
-                        return;               // sorted by shift: nothing further applies
-                    const float *p0 =
-                        reinterpret_cast<const float *>(pl - (size_t)((unsigned)ts[i] * 4u));
-                    if (ts[i + 1] > last) {
-#pragma unroll
-                        for (int j = 0; j < R; ++j)
-                            vmin(best[j], p0[j * kWave] + es[i]);
-                        return;
-                    }
-                    const float *p1 =
-                        reinterpret_cast<const float *>(pl - (size_t)((unsigned)ts[i + 1] * 4u));
-#pragma unroll
-                    for (int j = 0; j < R; ++j)
-                        vmin3(best[j], p0[j * kWave] + es[i], p1[j * kWave] + es[i + 1]);
                 }
             }
         }
-    };
-    sweep();
-
-    const int tl = t0 + lane;
+    } else {
+        // sorted by shift: the applicable levels are the first n_use
+        int n_use = 0;
+        for (int s0 = 0; s0 < s8; s0 += kBatch) {
 #pragma unroll
-    for (int j = 0; j < R; ++j) {
-        cur[tl + j * kWave] = best[j];
-        if constexpr (kLevel)
-            choice[tl + j * kWave] = (uint8_t)arg[j];
-        else
-            rec[tl + j * kWave] = best[j];
+            for (int i = 0; i < kBatch; ++i)
+                n_use += pp[s0 + i].shift <= last ? 1 : 0;
+        }
+        int s0 = 0;
+        for (; s0 + kBatch <= n_use; s0 += kBatch) {       // whole batches: no tests inside
+            int ts[kBatch];
+            float es[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                ts[i] = pp[s0 + i].shift;
+                es[i] = pp[s0 + i].err;
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; i += 2) {
+                const float *p0 = row_at(ts[i]);
+                const float *p1 = row_at(ts[i + 1]);
+#pragma unroll
+                for (int j = 0; j < R; ++j)
+                    vmin3(best[j], p0[j * kWave] + es[i], p1[j * kWave] + es[i + 1]);
+            }
+        }
+        const int rem = n_use - s0;                         // 0 .. kBatch - 1 levels left
+        if (rem > 0) {
+            int ts[kBatch];
+            float es[kBatch];
+#pragma unroll
+            for (int i = 0; i < kBatch; ++i) {
+                ts[i] = pp[s0 + i].shift;
+                es[i] = pp[s0 + i].err;
+            }
+#pragma unroll
+            for (int i = 0; i < kBatch; i += 2) {
+                if (i + 1 < rem) {
+                    const float *p0 = row_at(ts[i]);
+                    const float *p1 = row_at(ts[i + 1]);
+#pragma unroll
+                    for (int j = 0; j < R; ++j)
+                        vmin3(best[j], p0[j * kWave] + es[i], p1[j * kWave] + es[i + 1]);
+                } else if (i < rem) {
+                    const float *p0 = row_at(ts[i]);
+#pragma unroll
+                    for (int j = 0; j < R; ++j)
+                        vmin(best[j], p0[j * kWave] + es[i]);
+                }
+            }
+        }
     }
 }
 
-template <bool kLevel>
-__device__ __forceinline__ void fill_chunks_lds(const float *prev, float *cur, uint8_t *choice,
-                                                float *rec, const LevelPair *pairs_l, int s8,
-                                                int c, int c_end, int lane)
+// One group of one layer: sweep, store the record, and write the new row values to `cur`.
+// With `inplace` cur aliases prev, so a workgroup barrier separates the last read of the row
+// from the first write (every wave of the workgroup calls this exactly once per layer then,
+// with R = 0 if it has no chunks).
+template <int R, bool kLevel, bool inplace>
+__device__ __forceinline__ void fill_group_lds(const float *prev, float *cur, uint8_t *choice,
+                                               float *rec, const LevelPair *pairs_l, int s8,
+                                               int t0, int lane)
 {
-    while (c < c_end) {
-        const int n = c_end - c;
-        const int groups = (n + kMaxGroup - 1) / kMaxGroup;
-        const int r = (n + groups - 1) / groups;
-        const int t0 = c * kWave;
-        switch (r) {
-#define SPDY_CASE(RR)                                                                   \
-    case RR:                                                                            \
-        fill_group_lds<RR, kLevel>(prev, cur, choice, rec, pairs_l, s8, t0, lane);      \
-        break;
-            SPDY_CASE(1)
-            SPDY_CASE(2)
-            SPDY_CASE(3)
-            SPDY_CASE(4)
-            SPDY_CASE(5)
-            SPDY_CASE(6)
-            SPDY_CASE(7)
-            SPDY_CASE(8)
-            SPDY_CASE(9)
-            SPDY_CASE(10)
-#undef SPDY_CASE
+    if constexpr (R == 0) {
+        if (inplace)
+            __syncthreads();
+    } else {
+        float best[R];
+        unsigned arg[R];
+        sweep_group<R, kLevel>(prev, pairs_l, s8, t0, lane, best, arg);
+        const int tl = t0 + lane;
+#pragma unroll
+        for (int j = 0; j < R; ++j) {
+            if constexpr (kLevel)
+                choice[tl + j * kWave] = (uint8_t)arg[j];
+            else
+                rec[tl + j * kWave] = best[j];
         }
-        c += r;
+        if (inplace)
+            __syncthreads();
+#pragma unroll
+        for (int j = 0; j < R; ++j)
+            cur[tl + j * kWave] = best[j];
+    }
+}
+
+template <bool kLevel, bool inplace>
+__device__ __forceinline__ void fill_group_lds_n(int r, const float *prev, float *cur,
+                                                 uint8_t *choice, float *rec,
+                                                 const LevelPair *pairs_l, int s8, int t0,
+                                                 int lane)
+{
+    switch (r) {
+#define SPDY_CASE(RR)                                                                          \
+    case RR:                                                                                   \
+        fill_group_lds<RR, kLevel, inplace>(prev, cur, choice, rec, pairs_l, s8, t0, lane);    \
+        break;
+        SPDY_CASE(0)
+        SPDY_CASE(1)
+        SPDY_CASE(2)
+        SPDY_CASE(3)
+        SPDY_CASE(4)
+        SPDY_CASE(5)
+        SPDY_CASE(6)
+        SPDY_CASE(7)
+        SPDY_CASE(8)
+        SPDY_CASE(9)
+        SPDY_CASE(10)
+#undef SPDY_CASE
+#define SPDY_CASE(RR)                                                                          \
+    case RR:                                                                                   \
+        if constexpr (!kLevel)                                                                 \
+            fill_group_lds<RR, kLevel, inplace>(prev, cur, choice, rec, pairs_l, s8, t0, lane); \
+        break;
+        SPDY_CASE(11)
+        SPDY_CASE(12)
+        SPDY_CASE(13)
+#undef SPDY_CASE
     }
 }
 
@@ -488,6 +555,9 @@ __device__ __forceinline__ void fill_chunks(const float *prev, float *cur, uint8
             SPDY_CASE(8)
             SPDY_CASE(9)
             SPDY_CASE(10)
+            SPDY_CASE(11)
+            SPDY_CASE(12)
+            SPDY_CASE(13)
 #undef SPDY_CASE
         }
         c += r;
@@ -540,9 +610,11 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 }
 
 // ---------------------------------------------------------------------------------------------
-// Resident path: both reduced D rows of a candidate stay in LDS for all L layers.  The waves of a
-// workgroup form `teams` teams of `tw` waves; team i of workgroup b solves candidate
+// Resident path: the reduced D row(s) of a candidate stay in LDS for all L layers.  The waves of
+// a workgroup form `teams` teams of `tw` waves; team i of workgroup b solves candidate
 // b * teams + i.  Barriers are workgroup-wide, so every team steps through the layers together.
+// In-place mode (every wave holds all its chunks in registers): one row per team; a layer is
+// swept, barrier, written back, barrier.  Otherwise two rows alternate with one barrier a layer.
 // `pitch` is the record's row pitch; the record row of layer l is l + 1 (D) or l (levels).
 template <bool kLevel>
 __global__ __launch_bounds__(kResidentThreads, 8) void dp_fill_resident(
@@ -562,6 +634,7 @@ __global__ __launch_bounds__(kResidentThreads, 8) void dp_fill_resident(
     }
     const int teams = meta[kMetaTeams];
     const int tw = meta[kMetaTeamWaves];
+    const bool inplace = meta[kMetaInPlace] != 0;
     if ((long long)blockIdx.x * teams >= K)
         return;                                  // the first ceil(K / teams) workgroups suffice
     const int row = meta[kMetaRow];
@@ -572,35 +645,50 @@ __global__ __launch_bounds__(kResidentThreads, 8) void dp_fill_resident(
     const int k = blockIdx.x * teams + team;
     const bool active = team < teams && k < K;
     const int stride = kHalo + row;              // floats per LDS row incl. its apron
-    float *buf0 = lds + (size_t)(team < teams ? team : 0) * 2 * stride + kHalo;
-    float *buf1 = buf0 + stride;
+    const int team_floats = inplace ? stride : 2 * stride;
+    float *buf0 = lds + (size_t)(team < teams ? team : 0) * team_floats + kHalo;
+    float *buf1 = inplace ? buf0 : buf0 + stride;
 
     // D before the first layer: time 0 costs nothing, nothing else is reachable (Eq. 3 then is
     // the general update).  -0.0f + e returns e bit for bit for every e, +0.0f would not for
     // e = -0.0f.  Aprons and chunks a layer does not compute keep this +inf.
-    for (int i = tid; i < teams * 2 * stride; i += nthreads)
-        lds[i] = (i % (2 * stride) == kHalo) ? -0.0f : __builtin_inff();
+    for (int i = tid; i < teams * team_floats; i += nthreads)
+        lds[i] = (i % team_floats == kHalo) ? -0.0f : __builtin_inff();
     __syncthreads();
 
     const int32_t *nact = meta + kMetaHeader + L;
     const LevelPair *pairs_k = pairs + (size_t)(active ? k : 0) * L * s8;
 
     for (int l = 0; l < L; ++l) {
+        const float *prev = (l & 1) ? buf1 : buf0;
+        float *cur = (l & 1) ? buf0 : buf1;
+        int c = 0, c_end = 0;
         if (active) {
-            const float *prev = (l & 1) ? buf1 : buf0;
-            float *cur = (l & 1) ? buf0 : buf1;
             const int n = nact[l];               // chunks of this row that can be finite
-            const int c_begin = (int)((long long)wv * n / tw);
-            const int c_end = (int)((long long)(wv + 1) * n / tw);
-            uint8_t *choice_l = kLevel ? choice + ((size_t)k * L + l) * pitch : nullptr;
-            float *drec_l = kLevel ? nullptr : drec + ((size_t)k * (L + 1) + l + 1) * pitch;
-            fill_chunks_lds<kLevel>(prev, cur, choice_l, drec_l, pairs_k + (size_t)l * s8, s8,
-                                    c_begin, c_end, lane);
+            c = (int)((long long)wv * n / tw);
+            c_end = (int)((long long)(wv + 1) * n / tw);
+        }
+        uint8_t *choice_l = kLevel ? choice + ((size_t)k * L + l) * pitch : nullptr;
+        float *drec_l = kLevel ? nullptr : drec + ((size_t)k * (L + 1) + l + 1) * pitch;
+        const LevelPair *pairs_l = pairs_k + (size_t)l * s8;
+        constexpr int kMax = kLevel ? kMaxGroupLevel : kMaxGroup;
+        if (inplace) {                           // c_end - c <= kMax by construction
+            fill_group_lds_n<kLevel, true>(min(c_end - c, kMax), prev, cur, choice_l, drec_l,
+                                           pairs_l, s8, c * kWave, lane);
+        } else {
+            while (c < c_end) {
+                const int n = c_end - c;
+                const int groups = (n + kMax - 1) / kMax;
+                const int r = (n + groups - 1) / groups;
+                fill_group_lds_n<kLevel, false>(r, prev, cur, choice_l, drec_l, pairs_l, s8,
+                                                c * kWave, lane);
+                c += r;
+            }
         }
         __syncthreads();
     }
 
-    // final argmin over t' <= bp within each team; the other row (and its apron) is dead now
+    // final argmin over t' <= bp within each team; the apron (and a second row) is dead now
     const float *last = (L & 1) ? buf1 : buf0;
     float *scratch_v = ((L & 1) ? buf0 : buf1) - kHalo;
     int *scratch_t = reinterpret_cast<int *>(scratch_v) + kResidentWaves;
@@ -853,7 +941,7 @@ int launch_fill(const Layout &lay, const int32_t *tau, const float *err, int K, 
     const int nchunks = pitch / kWave;
     const int chunks_per_block = (kStreamThreads / kWave) * kStreamGroup;
     const int yblocks = (nchunks + chunks_per_block - 1) / chunks_per_block;
-    if (lay.may_stream && yblocks > 65535)
+    if ((lay.may_stream && yblocks > 65535) || (K + kStageCands - 1) / kStageCands > 65535)
         return SPDY_DP_ERR_OVERFLOW;
 
     // The reduced row length is only known on the device, so the resident kernel is enqueued
@@ -876,17 +964,13 @@ int launch_fill(const Layout &lay, const int32_t *tau, const float *err, int K, 
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_max) != hipSuccess)
         return SPDY_DP_ERR_LAUNCH;
     const int waves = nchunks < kResidentWaves ? nchunks : kResidentWaves;
-    uint8_t *order = reinterpret_cast<uint8_t *>(ws + lay.order_off);
     LevelPair *pairs = reinterpret_cast<LevelPair *>(ws + lay.pairs_off);
     const int s8 = (int)lay.s8;
 
-    hipLaunchKernelGGL(dp_prepare, dim3(1), dim3(256), 0, q, tau, L, S, B, waves, lds_small,
-                       lds_large, meta);
-    hipLaunchKernelGGL(dp_order_levels, dim3(L), dim3(256), 0, q, tau, S, kLevel ? 0 : 1, order);
-    const size_t n_pairs = (size_t)K * L * lay.s8;
-    const size_t stage_blocks = (n_pairs + 255) / 256;
-    hipLaunchKernelGGL(dp_stage_levels, dim3((unsigned)(stage_blocks < 65536 ? stage_blocks : 65536)),
-                       dim3(256), 0, q, tau, err, meta, order, K, L, S, s8, pairs);
+    hipLaunchKernelGGL(dp_prepare, dim3(1), dim3(256), 0, q, tau, L, S, B, waves,
+                       kLevel ? kMaxGroupLevel : kMaxGroup, lds_small, lds_large, meta);
+    hipLaunchKernelGGL(dp_stage_levels, dim3(L, (K + kStageCands - 1) / kStageCands), dim3(256),
+                       0, q, tau, err, K, L, S, s8, kLevel ? 0 : 1, pairs);
     hipLaunchKernelGGL(resident, dim3(K), dim3(waves * kWave), lds_small, q, pairs, meta, 1, K, L,
                        s8, pitch, choice, drec, tstar, cost);
     if (lds_large)

@@ -56,7 +56,7 @@ def test_workspace_size(binding):
     fast = binding.spdy_dp_workspace_bytes(K, L, S, B)
     small = binding.spdy_dp_workspace_bytes_min(K, L, S, B)
     # fp32 D per cell (one extra row per candidate) vs one byte per cell, rows padded to 64
-    staged = 8 * K * L * ((S + 7) // 8 * 8) + L * S     # (shift, err) pairs and visiting order
+    staged = 8 * K * L * ((S + 7) // 8 * 8)     # (shift, err) pair per (candidate, layer, level)
     assert 4 * K * (L + 1) * row + staged <= fast <= 4 * K * (L + 1) * row + staged + 16384
     assert K * L * row + staged <= small <= K * L * row + staged + 16384
     lay = binding.spdy_dp_workspace_layout(K, L, S, B, fast)

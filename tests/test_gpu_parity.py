@@ -83,8 +83,8 @@ def check_tables(dp, tau, err_k, B, ws, k, K):
     a = lay["record_offset"] + k * rows * pitch * esize
     rec = ws[a:a + rows * pitch * esize].cpu().numpy()
     rec = rec.view(np.float32 if esize == 4 else np.uint8).reshape(rows, pitch)
-    if meta[3] == 0:     # per-layer kernels ran: two reduced rows (plus aprons) exceed LDS
-        assert 2 * (meta[2] + 640) * 4 > 160 * 1024
+    if meta[3] == 0:     # per-layer kernels ran: the reduced rows (plus aprons) exceed LDS
+        assert 2 * (meta[2] + 832) * 4 > 160 * 1024
     for l in range(L):
         n = int(min(nact[l] * 64, bp + 1))
         want_D = D[l, lo[l]:lo[l] + n]
