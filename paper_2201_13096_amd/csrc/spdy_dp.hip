@@ -284,14 +284,34 @@ __device__ __forceinline__ void vmin3(float &b, float x, float y)
     asm("v_min3_f32 %0, %0, %1, %2" : "+v"(b) : "v"(x), "v"(y));
 }
 
+// This lane's entry of the 64 staged levels starting at level `blk` (padding past s8).
+__device__ __forceinline__ LevelPair load_level(const LevelPair *__restrict__ pairs_l, int s8,
+                                                int blk, int lane)
+{
+    LevelPair p;
+    p.shift = INT32_MAX;
+    p.err = __builtin_inff();
+    if (blk + lane < s8)
+        p = pairs_l[blk + lane];
+    return p;
+}
+
+__device__ __forceinline__ float lane_value(float v, int lane)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
+}
+
 // Resident path: the levels of one layer swept over one group of R chunks (R*64 consecutive
 // reduced buckets from t0); best[j] / arg[j] belong to bucket t0 + 64*j + lane.
 //   prev    : LDS row of the previous layer, prev[-kHalo .. -1] reads +inf
-//   pairs_l : the layer's s8 staged levels (64-byte aligned), sorted by shift unless kLevel
+//   first   : lane i holds staged level i of the layer (levels 0..63)
+//   pairs_l : the layer's s8 staged levels, sorted by shift unless kLevel (for levels >= 64)
 // A level applies to the group if its shift does not exceed the group's last bucket; lanes
-// left of the shift then read the +inf apron.
+// left of the shift then read the +inf apron.  The applicable levels of a 64-block are found
+// with one ballot and walked in ascending order; shift and error reach the scalar registers
+// with v_readlane, so the sweep issues no memory instruction besides the LDS reads.
 template <int R, bool kLevel>
-__device__ __forceinline__ void sweep_group(const float *__restrict__ prev,
+__device__ __forceinline__ void sweep_group(const float *__restrict__ prev, LevelPair first,
                                             const LevelPair *__restrict__ pairs_l, int s8, int t0,
                                             int lane, float (&best)[R], unsigned (&arg)[R])
 {
@@ -302,90 +322,51 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev,
     }
     const int last = t0 + R * kWave - 1;      // last bucket of the group
     const char *pl = reinterpret_cast<const char *>(prev + t0 + lane);
-    // the staged levels were written by an earlier kernel: read them through the constant
-    // address space so that the (wave-uniform) fetches become scalar loads
-    typedef const __attribute__((address_space(4))) LevelPair *ConstPairs;
-    const ConstPairs pp = (ConstPairs)(uintptr_t)__builtin_assume_aligned(pairs_l, kBatch * 8);
-
     auto row_at = [&](int shift) {
         return reinterpret_cast<const float *>(pl - (size_t)((unsigned)shift * 4u));
     };
 
-    if constexpr (kLevel) {
-        for (int s0 = 0; s0 < s8; s0 += kBatch) {
-            int ts[kBatch];
-            float es[kBatch];
-#pragma unroll
-            for (int i = 0; i < kBatch; ++i) {
-                ts[i] = pp[s0 + i].shift;
-                es[i] = pp[s0 + i].err;
-            }
-#pragma unroll
-            for (int i = 0; i < kBatch; ++i) {
-                // a level whose shift lies beyond the group is moved so that every lane reads
-                // the apron (+inf never wins a strict "<"): no branch, the order in s is kept
-                const float *p = row_at(min(ts[i], last + 1));
-                const unsigned s = (unsigned)(s0 + i);
+    for (int blk = 0; blk < s8; blk += kWave) {
+        const LevelPair mine = blk == 0 ? first : load_level(pairs_l, s8, blk, lane);
+        unsigned long long use = __ballot(mine.shift <= last);
+        if constexpr (kLevel) {
+            while (use) {
+                const int i = __builtin_ctzll(use);
+                use &= use - 1;
+                const float *p = row_at(__builtin_amdgcn_readlane(mine.shift, i));
+                const float e = lane_value(mine.err, i);
+                const unsigned s = (unsigned)(blk + i);
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
-                    const float v = p[j * kWave] + es[i];
+                    const float v = p[j * kWave] + e;
                     if (v < best[j]) {
                         best[j] = v;
                         arg[j] = s;
                     }
                 }
             }
-        }
-    } else {
-        // sorted by shift: the applicable levels are the first n_use
-        int n_use = 0;
-        for (int s0 = 0; s0 < s8; s0 += kBatch) {
-#pragma unroll
-            for (int i = 0; i < kBatch; ++i)
-                n_use += pp[s0 + i].shift <= last ? 1 : 0;
-        }
-        int s0 = 0;
-        for (; s0 + kBatch <= n_use; s0 += kBatch) {       // whole batches: no tests inside
-            int ts[kBatch];
-            float es[kBatch];
-#pragma unroll
-            for (int i = 0; i < kBatch; ++i) {
-                ts[i] = pp[s0 + i].shift;
-                es[i] = pp[s0 + i].err;
-            }
-#pragma unroll
-            for (int i = 0; i < kBatch; i += 2) {
-                const float *p0 = row_at(ts[i]);
-                const float *p1 = row_at(ts[i + 1]);
+        } else {
+            // sorted by shift: the applicable levels are the first n_use of the block
+            const int n_use = __builtin_popcountll(use);
+            int i = 0;
+            for (; i + 2 <= n_use; i += 2) {
+                const float *p0 = row_at(__builtin_amdgcn_readlane(mine.shift, i));
+                const float *p1 = row_at(__builtin_amdgcn_readlane(mine.shift, i + 1));
+                const float e0 = lane_value(mine.err, i);
+                const float e1 = lane_value(mine.err, i + 1);
 #pragma unroll
                 for (int j = 0; j < R; ++j)
-                    vmin3(best[j], p0[j * kWave] + es[i], p1[j * kWave] + es[i + 1]);
+                    vmin3(best[j], p0[j * kWave] + e0, p1[j * kWave] + e1);
             }
-        }
-        const int rem = n_use - s0;                         // 0 .. kBatch - 1 levels left
-        if (rem > 0) {
-            int ts[kBatch];
-            float es[kBatch];
+            if (i < n_use) {
+                const float *p0 = row_at(__builtin_amdgcn_readlane(mine.shift, i));
+                const float e0 = lane_value(mine.err, i);
 #pragma unroll
-            for (int i = 0; i < kBatch; ++i) {
-                ts[i] = pp[s0 + i].shift;
-                es[i] = pp[s0 + i].err;
+                for (int j = 0; j < R; ++j)
+                    vmin(best[j], p0[j * kWave] + e0);
             }
-#pragma unroll
-            for (int i = 0; i < kBatch; i += 2) {
-                if (i + 1 < rem) {
-                    const float *p0 = row_at(ts[i]);
-                    const float *p1 = row_at(ts[i + 1]);
-#pragma unroll
-                    for (int j = 0; j < R; ++j)
-                        vmin3(best[j], p0[j * kWave] + es[i], p1[j * kWave] + es[i + 1]);
-                } else if (i < rem) {
-                    const float *p0 = row_at(ts[i]);
-#pragma unroll
-                    for (int j = 0; j < R; ++j)
-                        vmin(best[j], p0[j * kWave] + es[i]);
-                }
-            }
+            if (n_use < kWave)
+                break;                        // later blocks only hold larger shifts
         }
     }
 }
@@ -396,8 +377,8 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev,
 // with R = 0 if it has no chunks).
 template <int R, bool kLevel, bool inplace>
 __device__ __forceinline__ void fill_group_lds(const float *prev, float *cur, uint8_t *choice,
-                                               float *rec, const LevelPair *pairs_l, int s8,
-                                               int t0, int lane)
+                                               float *rec, LevelPair first,
+                                               const LevelPair *pairs_l, int s8, int t0, int lane)
 {
     if constexpr (R == 0) {
         if (inplace)
@@ -405,7 +386,7 @@ __device__ __forceinline__ void fill_group_lds(const float *prev, float *cur, ui
     } else {
         float best[R];
         unsigned arg[R];
-        sweep_group<R, kLevel>(prev, pairs_l, s8, t0, lane, best, arg);
+        sweep_group<R, kLevel>(prev, first, pairs_l, s8, t0, lane, best, arg);
         const int tl = t0 + lane;
 #pragma unroll
         for (int j = 0; j < R; ++j) {
@@ -424,14 +405,15 @@ __device__ __forceinline__ void fill_group_lds(const float *prev, float *cur, ui
 
 template <bool kLevel, bool inplace>
 __device__ __forceinline__ void fill_group_lds_n(int r, const float *prev, float *cur,
-                                                 uint8_t *choice, float *rec,
+                                                 uint8_t *choice, float *rec, LevelPair first,
                                                  const LevelPair *pairs_l, int s8, int t0,
                                                  int lane)
 {
     switch (r) {
 #define SPDY_CASE(RR)                                                                          \
     case RR:                                                                                   \
-        fill_group_lds<RR, kLevel, inplace>(prev, cur, choice, rec, pairs_l, s8, t0, lane);    \
+        fill_group_lds<RR, kLevel, inplace>(prev, cur, choice, rec, first, pairs_l, s8, t0,    \
+                                            lane);                                             \
         break;
         SPDY_CASE(0)
         SPDY_CASE(1)
@@ -448,7 +430,8 @@ __device__ __forceinline__ void fill_group_lds_n(int r, const float *prev, float
 #define SPDY_CASE(RR)                                                                          \
     case RR:                                                                                   \
         if constexpr (!kLevel)                                                                 \
-            fill_group_lds<RR, kLevel, inplace>(prev, cur, choice, rec, pairs_l, s8, t0, lane); \
+            fill_group_lds<RR, kLevel, inplace>(prev, cur, choice, rec, first, pairs_l, s8,    \
+                                                t0, lane);                                     \
         break;
         SPDY_CASE(11)
         SPDY_CASE(12)
@@ -659,7 +642,12 @@ __global__ __launch_bounds__(kResidentThreads, 8) void dp_fill_resident(
     const int32_t *nact = meta + kMetaHeader + L;
     const LevelPair *pairs_k = pairs + (size_t)(active ? k : 0) * L * s8;
 
+    // lane i keeps staged level i of the layer being swept; the next layer's is fetched early
+    LevelPair next_first = load_level(pairs_k, s8, 0, lane);
     for (int l = 0; l < L; ++l) {
+        const LevelPair first = next_first;
+        if (l + 1 < L)
+            next_first = load_level(pairs_k + (size_t)(l + 1) * s8, s8, 0, lane);
         const float *prev = (l & 1) ? buf1 : buf0;
         float *cur = (l & 1) ? buf0 : buf1;
         int c = 0, c_end = 0;
@@ -674,14 +662,14 @@ __global__ __launch_bounds__(kResidentThreads, 8) void dp_fill_resident(
         constexpr int kMax = kLevel ? kMaxGroupLevel : kMaxGroup;
         if (inplace) {                           // c_end - c <= kMax by construction
             fill_group_lds_n<kLevel, true>(min(c_end - c, kMax), prev, cur, choice_l, drec_l,
-                                           pairs_l, s8, c * kWave, lane);
+                                           first, pairs_l, s8, c * kWave, lane);
         } else {
             while (c < c_end) {
                 const int n = c_end - c;
                 const int groups = (n + kMax - 1) / kMax;
                 const int r = (n + groups - 1) / groups;
-                fill_group_lds_n<kLevel, false>(r, prev, cur, choice_l, drec_l, pairs_l, s8,
-                                                c * kWave, lane);
+                fill_group_lds_n<kLevel, false>(r, prev, cur, choice_l, drec_l, first, pairs_l,
+                                                s8, c * kWave, lane);
                 c += r;
             }
         }
