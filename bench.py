@@ -57,6 +57,9 @@ def main() -> int:
     ap.add_argument("--record", choices=["d", "level"], default="d",
                     help="what the fill records per cell: fp32 D (fast) or the one-byte level")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy (a known-size reference for "
+                         "FETCH_SIZE / WRITE_SIZE counter runs)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (candidates would shard across GPUs with no "
@@ -91,6 +94,13 @@ def main() -> int:
         if ev_b is not None:
             ev_b.record()
         dp.spdy_dp_backtrace(tau_d, err_d, B, profile, cost, ws)
+
+    if args.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         step()

@@ -338,11 +338,11 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, Leve
                 const unsigned s = (unsigned)(blk + i);
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
+                    // strict "<" decides the level; the value is the min either way (the sign
+                    // of a zero may differ from a select's, the walk back re-sums the cost)
                     const float v = p[j * kWave] + e;
-                    if (v < best[j]) {
-                        best[j] = v;
-                        arg[j] = s;
-                    }
+                    arg[j] = v < best[j] ? s : arg[j];
+                    vmin(best[j], v);
                 }
             }
         } else {
@@ -800,12 +800,14 @@ __global__ __launch_bounds__(kStreamThreads) void dp_final_argmin(
 // ---------------------------------------------------------------------------------------------
 // Walk back (last loop of Alg. 1).
 
-// Level record: one lane per candidate, L dependent one-byte reads.
-__global__ void dp_backtrace_levels(const int32_t *__restrict__ tau,
+// Level record: one lane per candidate, L dependent one-byte reads; the cost is re-summed over
+// the profile in layer order (exactly the sum Alg. 1's strict "<" sweep carries to the cell).
+__global__ void dp_backtrace_levels(const int32_t *__restrict__ tau, const float *__restrict__ err,
                                     const int32_t *__restrict__ meta,
                                     const uint8_t *__restrict__ choice,
                                     const int32_t *__restrict__ tstar, int K, int L, int S,
-                                    int pitch, int16_t *__restrict__ profile)
+                                    int pitch, int16_t *__restrict__ profile,
+                                    float *__restrict__ cost)
 {
     const int k = blockIdx.x * blockDim.x + threadIdx.x;
     if (k >= K)
@@ -819,22 +821,68 @@ __global__ void dp_backtrace_levels(const int32_t *__restrict__ tau,
     }
     const int32_t *mn = meta + kMetaHeader;
     const uint8_t *choice_k = choice + (size_t)k * L * pitch;
+    bool ok = true;
     for (int l = L - 1; l >= 0; --l) {
         const int s = choice_k[(size_t)l * pitch + t];
         prof[l] = (int16_t)s;
-        if (s >= S)          // cannot happen on a filled table; never index tau out of range
+        if (s >= S) {        // cannot happen on a filled table; never index tau out of range
+            ok = false;
             break;
+        }
         t -= tau[(size_t)l * S + s] - mn[l];
-        if (t < 0)
+        if (t < 0) {
+            ok = false;
             break;
+        }
     }
+    if (!ok) {
+        cost[k] = __builtin_nanf("");
+        return;
+    }
+    __threadfence();
+    const float *err_k = err + (size_t)k * L * S;
+    float acc = -0.0f;
+    for (int l = 0; l < L; ++l)
+        acc += err_k[(size_t)l * S + prof[l]];
+    cost[k] = acc;
 }
 
 // D record: one wave per candidate.  At (l, t) the lanes try the levels in parallel: lane s
 // forms D_{l-1}[t - shift_s] + err[l][s] with the same single fp32 add as the fill and compares
 // it with D_l[t]; the lowest matching level is the one a strict "<" sweep would have kept.
+// Only the gather of D_{l-1} depends on t, so the shifts and errors of the next layer down are
+// fetched while that gather is in flight: one memory round trip per layer on the critical path.
 // The cost is then re-summed over the profile in layer order, which reproduces the sign of a
 // zero exactly as the level-tracking sweep would (min(+0, -0) is order-blind).
+constexpr int kLevelBlocks = 4;   // 64-level blocks a lane can hold (S <= 255)
+
+struct LayerLevels {
+    int shift[kLevelBlocks];      // tau[l][s] - m_l for s = 64 b + lane (INT32_MAX past S)
+    float err[kLevelBlocks];
+    int reach;                    // computed buckets of row l - 1 (1 for l = 0: only t = 0)
+};
+
+__device__ __forceinline__ LayerLevels load_layer(const int32_t *__restrict__ tau,
+                                                  const float *__restrict__ err_k,
+                                                  const int32_t *__restrict__ meta, int l, int L,
+                                                  int S, int lane)
+{
+    LayerLevels v;
+    const int m = meta[kMetaHeader + l];
+    v.reach = l > 0 ? meta[kMetaHeader + L + l - 1] * kWave : 1;
+#pragma unroll
+    for (int b = 0; b < kLevelBlocks; ++b) {
+        const int s = b * kWave + lane;
+        v.shift[b] = INT32_MAX;
+        v.err[b] = __builtin_inff();
+        if (s < S) {
+            v.shift[b] = tau[(size_t)l * S + s] - m;
+            v.err[b] = err_k[(size_t)l * S + s];
+        }
+    }
+    return v;
+}
+
 __global__ __launch_bounds__(kStreamThreads) void dp_backtrace_values(
     const int32_t *__restrict__ tau, const float *__restrict__ err,
     const int32_t *__restrict__ meta, const float *__restrict__ drec,
@@ -852,38 +900,37 @@ __global__ __launch_bounds__(kStreamThreads) void dp_backtrace_values(
             prof[l] = -1;
         return;
     }
-    const int32_t *mn = meta + kMetaHeader;
-    const int32_t *nact = meta + kMetaHeader + L;
     const float *drec_k = drec + (size_t)k * (L + 1) * pitch;
     const float *err_k = err + (size_t)k * L * S;
     float target = drec_k[(size_t)L * pitch + t];
+    LayerLevels next = load_layer(tau, err_k, meta, L - 1, L, S, lane);
     bool ok = true;
     for (int l = L - 1; l >= 0; --l) {
-        const int m = mn[l];
-        const int reach = l > 0 ? nact[l - 1] * kWave : 1;   // computed buckets of row l - 1
+        const LayerLevels cur = next;
+        if (l > 0)
+            next = load_layer(tau, err_k, meta, l - 1, L, S, lane);
         const float *prow = drec_k + (size_t)l * pitch;      // record row l = layer l - 1
         int found = -1, next_t = 0;
         float next_target = 0.0f;
-        for (int s0 = 0; s0 < S && found < 0; s0 += kWave) {
-            const int s = s0 + lane;
-            bool match = false;
-            int u = 0;
-            float pv = __builtin_inff();
-            if (s < S) {
-                const long long uu = (long long)t - ((long long)tau[(size_t)l * S + s] - m);
-                if (uu >= 0 && uu < reach) {
+#pragma unroll
+        for (int b = 0; b < kLevelBlocks; ++b) {
+            if (b * kWave < S && found < 0) {
+                bool match = false;
+                int u = 0;
+                float pv = __builtin_inff();
+                const long long uu = (long long)t - cur.shift[b];
+                if (uu >= 0 && uu < cur.reach) {
                     u = (int)uu;
                     pv = l > 0 ? prow[u] : -0.0f;
-                    const float v = pv + err_k[(size_t)l * S + s];
-                    match = v == target;
+                    match = pv + cur.err[b] == target;
                 }
-            }
-            const unsigned long long mask = __ballot(match);
-            if (mask) {
-                const int first = __builtin_ctzll(mask);
-                found = s0 + first;
-                next_t = __shfl(u, first, kWave);
-                next_target = __shfl(pv, first, kWave);
+                const unsigned long long mask = __ballot(match);
+                if (mask) {
+                    const int first = __builtin_ctzll(mask);
+                    found = b * kWave + first;
+                    next_t = __shfl(u, first, kWave);
+                    next_target = __shfl(pv, first, kWave);
+                }
             }
         }
         if (found < 0) {     // cannot happen on a filled record
@@ -1065,8 +1112,8 @@ int spdy_dp_backtrace(const int32_t *tau, const float *err, int K, int L, int S,
     (void)hipGetLastError();
     if (lay.variant == kLevelRecord) {
         hipLaunchKernelGGL(dp_backtrace_levels, dim3((K + kWave - 1) / kWave), dim3(kWave), 0, q,
-                           tau, meta, reinterpret_cast<const uint8_t *>(ws + lay.record_off),
-                           tstar, K, L, S, (int)lay.row, profile);
+                           tau, err, meta, reinterpret_cast<const uint8_t *>(ws + lay.record_off),
+                           tstar, K, L, S, (int)lay.row, profile, cost);
     } else {
         const int per_block = kStreamThreads / kWave;
         hipLaunchKernelGGL(dp_backtrace_values, dim3((K + per_block - 1) / per_block),
