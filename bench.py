@@ -56,6 +56,8 @@ def main() -> int:
     ap.add_argument("--workload", default="rn50_k1024")
     ap.add_argument("--record", choices=["d", "level"], default="d",
                     help="what the fill records per cell: fp32 D (fast) or the one-byte level")
+    ap.add_argument("--candidates", type=int, default=None,
+                    help="solve only the first N candidates of the workload (experiments)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for "
@@ -77,7 +79,7 @@ def main() -> int:
     dp.binding.lib()
 
     cfg = workloads.CONFIGS[args.workload]
-    tau, err, B = workloads.generate(cfg)
+    tau, err, B = workloads.generate(cfg, K=args.candidates)
     K, L, S = err.shape
     dev = torch.device("cuda:0")
     tau_d = torch.from_numpy(tau).to(dev)
@@ -117,7 +119,7 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     fill_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
 
-    nominal = cfg.cell_updates                       # K*L*S*B
+    nominal = K * L * S * B
     executed = K * executed_updates_per_candidate(tau, B)
     value = nominal / (ms_per_step * 1e-3)
     ops = LANE_OPS_PER_UPDATE[args.record]

@@ -133,6 +133,35 @@ Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes)
     return lay;
 }
 
+// Sum of `v` over a workgroup of 256 threads (returned to every thread); if `exclusive` is given
+// it receives the sum over the threads before this one.  part: 8 words of LDS.
+__device__ __forceinline__ long long block_scan_256(long long v, long long *part,
+                                                    long long *exclusive)
+{
+    const int lane = threadIdx.x & (kWave - 1), wave = threadIdx.x / kWave;
+    long long incl = v;
+#pragma unroll
+    for (int off = 1; off < kWave; off <<= 1) {
+        const long long o = __shfl_up(incl, off, kWave);
+        if (lane >= off)
+            incl += o;
+    }
+    __syncthreads();                              // part may still be read from a previous call
+    if (lane == kWave - 1)
+        part[wave] = incl;
+    __syncthreads();
+    long long before = 0, total = 0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) {
+        const long long p = part[w];
+        before += w < wave ? p : 0;
+        total += p;
+    }
+    if (exclusive)
+        *exclusive = before + incl - v;
+    return total;
+}
+
 // ---------------------------------------------------------------------------------------------
 // Prepare: per-layer smallest time m_l, M = sum m_l, reduced budget B - M, and how many 64-bucket
 // chunks of each reduced row can hold a finite value (largest reachable reduced time after
@@ -144,7 +173,7 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
                                                   int B, int waves, int max_group, int lds_small,
                                                   int lds_large, int32_t *__restrict__ meta)
 {
-    __shared__ long long s_sum[256];
+    __shared__ long long s_sum[8];
     __shared__ int s_budget;
     const int tid = threadIdx.x;
     int32_t *mn = meta + kMetaHeader;
@@ -154,18 +183,23 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
 
     long long local = 0;
     for (int l = l0; l < l1; ++l) {
+        const int32_t *tau_l = tau + (size_t)l * S;
         int m = INT32_MAX;
-        for (int s = 0; s < S; ++s)
-            m = min(m, tau[(size_t)l * S + s]);
+        for (int s0 = 0; s0 < S; s0 += 8) {       // eight loads in flight per round trip
+            int v[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                v[i] = tau_l[min(s0 + i, S - 1)];
+#pragma unroll
+            for (int i = 0; i < 8; ++i)
+                m = min(m, v[i]);
+        }
         mn[l] = m;
         local += m;
     }
-    s_sum[tid] = local;
-    __syncthreads();
+    const long long M_all = block_scan_256(local, s_sum, nullptr);
     if (tid == 0) {
-        long long M = 0;
-        for (int i = 0; i < 256; ++i)
-            M += s_sum[i];
+        const long long M = M_all;
         const int bp = (M > B) ? -1 : (int)(B - M);
         const int rowp = bp < 0 ? 0 : (bp + kWave) / kWave * kWave;
         meta[kMetaBudget] = bp;
@@ -199,28 +233,26 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
     for (int l = l0; l < l1; ++l) {
         int span = 0;
         if (bp >= 0) {
+            const int32_t *tau_l = tau + (size_t)l * S;
             const int m = mn[l];
-            for (int s = 0; s < S; ++s) {
-                const long long d = (long long)tau[(size_t)l * S + s] - m;
-                if (d <= bp)
-                    span = max(span, (int)d);
+            for (int s0 = 0; s0 < S; s0 += 8) {
+                int v[8];
+#pragma unroll
+                for (int i = 0; i < 8; ++i)
+                    v[i] = tau_l[min(s0 + i, S - 1)];
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    const long long d = (long long)v[i] - m;
+                    if (d <= bp)
+                        span = max(span, (int)d);
+                }
             }
         }
         nact[l] = span;
         local += span;
     }
-    s_sum[tid] = local;
-    __syncthreads();
-    if (tid == 0) {                               // exclusive scan of the slices' sums
-        long long h = 0;
-        for (int i = 0; i < 256; ++i) {
-            const long long v = s_sum[i];
-            s_sum[i] = h;
-            h += v;
-        }
-    }
-    __syncthreads();
-    long long h = s_sum[tid];
+    long long h = 0;                              // sum of the slices before this thread's
+    block_scan_256(local, s_sum, &h);
     for (int l = l0; l < l1; ++l) {
         h += nact[l];
         const long long top = h < bp ? h : bp;
@@ -854,20 +886,20 @@ __global__ void dp_backtrace_levels(const int32_t *__restrict__ tau, const float
 // fetched while that gather is in flight: one memory round trip per layer on the critical path.
 // The cost is then re-summed over the profile in layer order, which reproduces the sign of a
 // zero exactly as the level-tracking sweep would (min(+0, -0) is order-blind).
-constexpr int kLevelBlocks = 4;   // 64-level blocks a lane can hold (S <= 255)
-
+// kLevelBlocks: 64-level blocks a lane holds (1 for S <= 64, 4 for S <= 255).
+template <int kLevelBlocks>
 struct LayerLevels {
     int shift[kLevelBlocks];      // tau[l][s] - m_l for s = 64 b + lane (INT32_MAX past S)
     float err[kLevelBlocks];
     int reach;                    // computed buckets of row l - 1 (1 for l = 0: only t = 0)
 };
 
-__device__ __forceinline__ LayerLevels load_layer(const int32_t *__restrict__ tau,
-                                                  const float *__restrict__ err_k,
-                                                  const int32_t *__restrict__ meta, int l, int L,
-                                                  int S, int lane)
+template <int kLevelBlocks>
+__device__ __forceinline__ LayerLevels<kLevelBlocks> load_layer(
+    const int32_t *__restrict__ tau, const float *__restrict__ err_k,
+    const int32_t *__restrict__ meta, int l, int L, int S, int lane)
 {
-    LayerLevels v;
+    LayerLevels<kLevelBlocks> v;
     const int m = meta[kMetaHeader + l];
     v.reach = l > 0 ? meta[kMetaHeader + L + l - 1] * kWave : 1;
 #pragma unroll
@@ -883,6 +915,7 @@ __device__ __forceinline__ LayerLevels load_layer(const int32_t *__restrict__ ta
     return v;
 }
 
+template <int kLevelBlocks>
 __global__ __launch_bounds__(kStreamThreads) void dp_backtrace_values(
     const int32_t *__restrict__ tau, const float *__restrict__ err,
     const int32_t *__restrict__ meta, const float *__restrict__ drec,
@@ -903,33 +936,38 @@ __global__ __launch_bounds__(kStreamThreads) void dp_backtrace_values(
     const float *drec_k = drec + (size_t)k * (L + 1) * pitch;
     const float *err_k = err + (size_t)k * L * S;
     float target = drec_k[(size_t)L * pitch + t];
-    LayerLevels next = load_layer(tau, err_k, meta, L - 1, L, S, lane);
+    LayerLevels<kLevelBlocks> next = load_layer<kLevelBlocks>(tau, err_k, meta, L - 1, L, S, lane);
     bool ok = true;
     for (int l = L - 1; l >= 0; --l) {
-        const LayerLevels cur = next;
-        if (l > 0)
-            next = load_layer(tau, err_k, meta, l - 1, L, S, lane);
+        const LayerLevels<kLevelBlocks> cur = next;
         const float *prow = drec_k + (size_t)l * pitch;      // record row l = layer l - 1
+        // issue the gather of D_{l-1} first, then the next layer's table behind it
+        int u[kLevelBlocks];
+        float pv[kLevelBlocks];
+        bool valid[kLevelBlocks];
+#pragma unroll
+        for (int b = 0; b < kLevelBlocks; ++b) {
+            const long long uu = (long long)t - cur.shift[b];
+            valid[b] = b * kWave < S && uu >= 0 && uu < cur.reach;
+            u[b] = valid[b] ? (int)uu : 0;
+            pv[b] = __builtin_inff();
+            if (valid[b])
+                pv[b] = l > 0 ? prow[u[b]] : -0.0f;
+        }
+        if (l > 0)
+            next = load_layer<kLevelBlocks>(tau, err_k, meta, l - 1, L, S, lane);
         int found = -1, next_t = 0;
         float next_target = 0.0f;
 #pragma unroll
         for (int b = 0; b < kLevelBlocks; ++b) {
             if (b * kWave < S && found < 0) {
-                bool match = false;
-                int u = 0;
-                float pv = __builtin_inff();
-                const long long uu = (long long)t - cur.shift[b];
-                if (uu >= 0 && uu < cur.reach) {
-                    u = (int)uu;
-                    pv = l > 0 ? prow[u] : -0.0f;
-                    match = pv + cur.err[b] == target;
-                }
+                const bool match = valid[b] && pv[b] + cur.err[b] == target;
                 const unsigned long long mask = __ballot(match);
                 if (mask) {
                     const int first = __builtin_ctzll(mask);
                     found = b * kWave + first;
-                    next_t = __shfl(u, first, kWave);
-                    next_target = __shfl(pv, first, kWave);
+                    next_t = __shfl(u[b], first, kWave);
+                    next_target = __shfl(pv[b], first, kWave);
                 }
             }
         }
@@ -1116,8 +1154,9 @@ int spdy_dp_backtrace(const int32_t *tau, const float *err, int K, int L, int S,
                            tstar, K, L, S, (int)lay.row, profile, cost);
     } else {
         const int per_block = kStreamThreads / kWave;
-        hipLaunchKernelGGL(dp_backtrace_values, dim3((K + per_block - 1) / per_block),
-                           dim3(kStreamThreads), 0, q, tau, err, meta,
+        hipLaunchKernelGGL(S <= kWave ? dp_backtrace_values<1> : dp_backtrace_values<4>,
+                           dim3((K + per_block - 1) / per_block), dim3(kStreamThreads), 0, q, tau,
+                           err, meta,
                            reinterpret_cast<const float *>(ws + lay.record_off), tstar, K, L, S,
                            (int)lay.row, profile, cost);
     }
