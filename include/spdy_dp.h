@@ -70,13 +70,13 @@ extern "C" {
 #define SPDY_DP_ERR_LAUNCH (-9)    /* the HIP runtime refused a launch (see hipGetLastError)    */
 
 /* Bytes of device workspace for the fast variant (fp32 D recorded per cell), or 0 if the sizes
- * are invalid.  About 4 * K * (L + 1) * (B + 1) + 8 * K * L * S bytes. */
+ * are invalid.  About 4 * K * L * (B + 1) bytes, plus 8 * K * (B + 1) when two rows of B + 1 floats
+ * exceed the 160 KB of LDS of a compute unit. */
 size_t spdy_dp_workspace_bytes(int K, int L, int S, int B);
 
 /* Smallest workspace accepted (one-byte level record per cell), or 0 if the sizes are invalid.
- * About K * L * (B + 1) + 8 * K * L * S bytes, plus 8 * K * (B + 1) when two rows of B + 1
- * floats exceed the 160 KB of LDS of a compute unit.  Any size in between selects this variant
- * too. */
+ * About K * L * (B + 1) bytes, plus the same 8 * K * (B + 1) for long rows.  Any size in between
+ * selects this variant too. */
 size_t spdy_dp_workspace_bytes_min(int K, int L, int S, int B);
 
 /* Solve all K candidates: the whole of Alg. 1 (table fill, final argmin over t, walk back).
@@ -112,9 +112,8 @@ int spdy_dp_backtrace(const int32_t *tau, const float *err, int K, int L, int S,
  *   out[2] byte offset of int32 t*[K] (reduced time t* - M, or -1 if infeasible)
  *   out[3] byte offset of the record
  *   out[4] record pitch in elements (buckets per row, a multiple of 64)
- *   out[5] record rows per candidate: L + 1 for the D record (row l + 1 holds layer l, row 0 the
- *          state before the first layer when rows live in global memory), L for the level record
- * Element (k, r, t') of the record is at out[3] + ((k * out[5] + r) * out[4] + t') * elemsize.
+ *   out[5] record rows per candidate (L: row l holds layer l)
+ * Element (k, l, t') of the record is at out[3] + ((k * out[5] + l) * out[4] + t') * elemsize.
  * Returns SPDY_DP_OK or a size / workspace error. */
 int spdy_dp_workspace_layout(int K, int L, int S, int B, size_t workspace_bytes, size_t out[6]);
 

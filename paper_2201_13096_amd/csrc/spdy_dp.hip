@@ -6,27 +6,27 @@
 // Mapping.  Alg. 1's triple loop (layer, level, time) is a min-plus recurrence with no reuse of a
 // D_{l-1} element across levels (every level shifts the row by a different tau), so there is no
 // contraction to put on the matrix cores: the work per (l, s, t) is one LDS read, one fp32 add
-// and a min (plus a compare and selects when the level itself is tracked).  The remark after
+// and a min (plus a compare and a select when the level itself is tracked).  The remark after
 // Alg. 1 (vectorise over t by shifting the row) is what the lanes do here:
 //   * a prepare kernel subtracts each layer's smallest time from the layer and from the budget
-//     (rows shrink to B - M + 1 buckets) and bounds the reachable part of each row;
-//   * one workgroup owns one candidate; its two live D rows (previous / current layer) stay in
-//     LDS for the whole solve and swap roles after every layer (one barrier per layer);
+//     (rows shrink to B - M + 1 buckets), bounds the reachable part of each row and fixes the
+//     order in which the levels of a layer are visited;
+//   * the row of D of a candidate stays in LDS for the whole solve, with a +inf apron of one
+//     group width on its left, so a level whose shift falls inside a group of buckets needs no
+//     per-lane bounds test; levels whose shift lies beyond the group are never visited;
 //   * the time axis is cut into chunks of 64 buckets; lane i of a wave works on bucket
 //     64*c + i of a chunk, so every ds_read_b32 of the shifted row touches 64 consecutive
 //     dwords (conflict-free for any shift) and every store of the record is 64 consecutive
 //     elements;
 //   * a wave keeps R chunks in registers (running minimum, and the level when tracked, for R
-//     buckets per lane) and sweeps the levels once; (shift, error) pairs of a layer are staged
-//     per candidate, sorted by shift when only the minimum is needed, and fetched eight at a
-//     time with one scalar load;
-//   * each LDS row has a +inf apron of one group width on its left, so a level whose shift
-//     falls inside the group needs no per-lane bounds test; levels whose shift lies beyond the
-//     group are skipped with a scalar compare;
+//     buckets per lane) and sweeps the levels once; lane i holds the i-th level of the layer,
+//     one ballot finds the applicable levels and v_readlane moves shift and error to scalar
+//     registers, so the sweep issues no memory instruction besides the LDS reads;
 //   * a workgroup of 16 waves is split at run time into teams, one candidate per team, so that
-//     each wave owns about ten chunks whatever the reduced row length is.
-// When two reduced rows do not fit in LDS a per-group routine with per-lane bounds tests runs
-// from per-layer launches with the rows in global memory.
+//     each wave owns about ten chunks whatever the reduced row length is; when every wave holds
+//     all its chunks of the row in registers the row is updated in place (one row per
+//     candidate), otherwise two rows alternate.
+// When not even one reduced row fits in LDS the same kernel runs with the rows in global memory.
 #include <hip/hip_runtime.h>
 
 #include <stdint.h>
@@ -38,31 +38,25 @@ namespace {
 constexpr int kWave = 64;            // lanes per wavefront = buckets per chunk
 constexpr int kMaxGroup = 13;        // most chunks a wave keeps in registers at once (D record)
 constexpr int kMaxGroupLevel = 10;   // same when the level is tracked too (more registers each)
-constexpr int kResidentThreads = 1024;
-constexpr int kResidentWaves = kResidentThreads / kWave;
-constexpr int kStreamThreads = 256;  // per-layer kernel: 4 waves per workgroup
-constexpr int kStreamGroup = 8;      // chunks per wave in the per-layer kernel
-constexpr int kLdsBytes = 160 * 1024;
-constexpr int kLdsHalf = kLdsBytes / 2;   // lets two workgroups share a compute unit
-constexpr int kHalo = kMaxGroup * kWave;  // +inf apron left of every LDS row (one group width)
-constexpr int kBatch = 8;                 // levels fetched per scalar load
+constexpr int kFillThreads = 1024;
+constexpr int kFillWaves = kFillThreads / kWave;
+constexpr int kWalkThreads = 256;    // D-record walk back: 4 waves = 4 candidates per workgroup
+constexpr int kLdsStatic = 256;           // room for the fill kernel's static LDS (argmin scratch)
+constexpr int kLdsBytes = 160 * 1024 - kLdsStatic;       // dynamic LDS a workgroup can get
+constexpr int kLdsHalf = 80 * 1024 - kLdsStatic;         // lets two workgroups share a compute unit
+constexpr int kHalo = kMaxGroup * kWave;  // +inf apron left of every row (one group width)
+constexpr int kBatch = 8;                 // level tables are padded to a multiple of this
 constexpr unsigned kNoLevel = 0xFF;
 constexpr size_t kAlign = 256;
 constexpr int kMetaHeader = 8;       // int32 words before the per-layer arrays
 
-// kMetaPath: 0 = per-layer kernels, 1 / 2 = LDS-resident kernel launched with the smaller /
-// larger LDS allocation.  kMetaTeamWaves x kMetaTeams <= waves of a resident workgroup.
-// kMetaInPlace: every wave of a team holds all its chunks of a row in registers, so one LDS
-// row per candidate suffices (written back between two barriers); otherwise two rows alternate.
+// kMetaPath: 0 = rows in global memory, 1 / 2 = rows in LDS, fill kernel launched with the
+// smaller / larger LDS allocation.  kMetaTeamWaves x kMetaTeams <= waves of a fill workgroup.
+// kMetaInPlace: every wave of a team holds all its chunks of a row in registers, so one row per
+// candidate suffices (written back between two barriers); otherwise two rows alternate.
 enum MetaWord {
     kMetaBudget = 0, kMetaMinTime = 1, kMetaRow = 2, kMetaPath = 3, kMetaTeamWaves = 4,
     kMetaTeams = 5, kMetaInPlace = 6
-};
-constexpr int kStageCands = 64;      // candidates staged per workgroup of dp_stage_levels
-
-struct LevelPair {   // one level of one layer of one candidate, as the resident kernel reads it
-    int32_t shift;   // tau[l][s] - m_l  (INT32_MAX in padding entries)
-    float err;
 };
 
 enum Variant { kValueRecord = 0, kLevelRecord = 1 };
@@ -73,13 +67,15 @@ struct Layout {
     int status;
     int variant;
     size_t row;          // buckets per padded row for the full budget (multiple of 64)
-    bool may_stream;     // two rows of the full budget exceed LDS: the per-layer path may run
-    size_t meta_off;     // int32 meta[kMetaHeader + 2 L]
-    size_t tstar_off;    // int32 tstar[K]
+    bool may_spill;      // rows of the full budget may exceed LDS: the global-row launch is needed
     size_t s8;           // levels per layer padded to a multiple of kBatch
-    size_t pairs_off;    // LevelPair pairs[K][L][s8]
-    size_t record_off;   // float D[K][L+1][row]  or  uint8 P[K][L][row]
-    size_t rows_off;     // float D[2][K][row], level record with may_stream only
+    size_t meta_off;     // int32 meta[kMetaHeader + 2 L]
+    size_t shifts_off;   // int32 shifts[L][s8]: tau - m_l of the r-th visited level
+    size_t order_off;    // int32 order[L][s8]: index of the r-th visited level
+    size_t tstar_off;    // int32 tstar[K]
+    size_t record_off;   // float D[K][L][row]  or  uint8 P[K][L][row]
+    size_t rows_value;   // float rows[K][2][kHalo + row] after the record, when may_spill
+    size_t rows_level;
     size_t total_value;  // bytes needed by the D-record variant
     size_t total_level;  // bytes needed by the level-record variant
 };
@@ -103,24 +99,26 @@ Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes)
         return lay;
     }
     lay.row = align_up((size_t)B + 1, kWave);
-    const unsigned __int128 cells = (unsigned __int128)K * ((unsigned __int128)L + 1) * lay.row;
-    if (cells * sizeof(float) + (unsigned __int128)K * L * 2048 + (unsigned __int128)K * 16 +
-            (unsigned __int128)L * 512 >
+    const unsigned __int128 cells = (unsigned __int128)K * ((unsigned __int128)L + 2) *
+                                    (lay.row + kHalo);
+    if (cells * sizeof(float) + (unsigned __int128)K * 16 + (unsigned __int128)L * 4096 >
         (unsigned __int128)1 << 62) {
         lay.status = SPDY_DP_ERR_OVERFLOW;
         return lay;
     }
-    lay.may_stream = 2 * (lay.row + kHalo) * sizeof(float) > (size_t)kLdsBytes;
+    const size_t row_bytes = (lay.row + kHalo) * sizeof(float);
+    lay.may_spill = 2 * row_bytes > (size_t)kLdsBytes;
     lay.s8 = align_up((size_t)S, kBatch);
     lay.meta_off = 0;
-    lay.tstar_off = align_up((kMetaHeader + 2 * (size_t)L) * sizeof(int32_t), kAlign);
-    lay.pairs_off = align_up(lay.tstar_off + (size_t)K * sizeof(int32_t), kAlign);
-    lay.record_off =
-        align_up(lay.pairs_off + (size_t)K * L * lay.s8 * sizeof(LevelPair), kAlign);
-    lay.total_value = lay.record_off + (size_t)K * ((size_t)L + 1) * lay.row * sizeof(float);
-    lay.rows_off = align_up(lay.record_off + (size_t)K * L * lay.row, kAlign);
-    lay.total_level =
-        lay.may_stream ? lay.rows_off + 2 * (size_t)K * lay.row * sizeof(float) : lay.rows_off;
+    lay.shifts_off = align_up((kMetaHeader + 2 * (size_t)L) * sizeof(int32_t), kAlign);
+    lay.order_off = align_up(lay.shifts_off + (size_t)L * lay.s8 * sizeof(int32_t), kAlign);
+    lay.tstar_off = align_up(lay.order_off + (size_t)L * lay.s8 * sizeof(int32_t), kAlign);
+    lay.record_off = align_up(lay.tstar_off + (size_t)K * sizeof(int32_t), kAlign);
+    const size_t rows = lay.may_spill ? 2 * (size_t)K * row_bytes : 0;
+    lay.rows_value = align_up(lay.record_off + (size_t)K * L * lay.row * sizeof(float), kAlign);
+    lay.rows_level = align_up(lay.record_off + (size_t)K * L * lay.row, kAlign);
+    lay.total_value = lay.rows_value + rows;
+    lay.total_level = lay.rows_level + rows;
     if (workspace_bytes >= lay.total_value)
         lay.variant = kValueRecord;
     else if (workspace_bytes >= lay.total_level)
@@ -133,6 +131,7 @@ Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes)
     return lay;
 }
 
+// ---------------------------------------------------------------------------------------------
 // Sum of `v` over a workgroup of 256 threads (returned to every thread); if `exclusive` is given
 // it receives the sum over the threads before this one.  part: 8 words of LDS.
 __device__ __forceinline__ long long block_scan_256(long long v, long long *part,
@@ -162,16 +161,15 @@ __device__ __forceinline__ long long block_scan_256(long long v, long long *part
     return total;
 }
 
-// ---------------------------------------------------------------------------------------------
-// Prepare: per-layer smallest time m_l, M = sum m_l, reduced budget B - M, and how many 64-bucket
-// chunks of each reduced row can hold a finite value (largest reachable reduced time after
-// layer l is sum_{j<=l} max_s (tau[j][s] - m_j) over the levels that fit the reduced budget).
-// It also picks the path: which launch of the resident kernel (LDS allocation lds_small or
-// lds_large bytes, `waves` waves per workgroup) fits, into how many teams its waves split, and
-// whether one LDS row per candidate is enough.  One workgroup; thread i owns a slice of layers.
-__global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ tau, int L, int S,
-                                                  int B, int waves, int max_group, int lds_small,
-                                                  int lds_large, int32_t *__restrict__ meta)
+// Prepare, workgroup 0: per-layer smallest time m_l, M = sum m_l, reduced budget B - M, and how
+// many 64-bucket chunks of each reduced row can hold a finite value (the largest reachable
+// reduced time after layer l is sum_{j<=l} max_s (tau[j][s] - m_j) over the levels that fit the
+// reduced budget).  It also picks the path: which launch of the fill kernel (LDS allocation
+// lds_small or lds_large bytes, `waves` waves per workgroup) fits, into how many teams its waves
+// split, and whether one row per candidate is enough.  Thread i owns a slice of layers.
+__device__ void prepare_budget(const int32_t *__restrict__ tau, int L, int S, int B, int waves,
+                               int max_group, int lds_small, int lds_large,
+                               int32_t *__restrict__ meta)
 {
     __shared__ long long s_sum[8];
     __shared__ int s_budget;
@@ -197,9 +195,8 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
         mn[l] = m;
         local += m;
     }
-    const long long M_all = block_scan_256(local, s_sum, nullptr);
+    const long long M = block_scan_256(local, s_sum, nullptr);
     if (tid == 0) {
-        const long long M = M_all;
         const int bp = (M > B) ? -1 : (int)(B - M);
         const int rowp = bp < 0 ? 0 : (bp + kWave) / kWave * kWave;
         meta[kMetaBudget] = bp;
@@ -213,6 +210,8 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
             const long long team_lds = inplace ? one_row : 2 * one_row;
             const int lds = team_lds <= lds_small ? lds_small : lds_large;
             path = team_lds <= lds_small ? 1 : (team_lds <= lds_large ? 2 : 0);
+            if (path == 0)
+                inplace = 0;                      // rows in global memory always alternate
             if (path != 0 && inplace) {
                 // as many candidates per workgroup as keeps every wave at <= max_group chunks
                 teams = waves / want;
@@ -260,51 +259,51 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
     }
 }
 
-// ---------------------------------------------------------------------------------------------
-// Stage the levels for the resident kernel: pairs[k][l][r] = (tau[l][s] - m_l, err[k][l][s])
-// where s is the r-th level in visiting order; padding up to s8 is (INT32_MAX, +inf), which no
-// group of buckets can use.  When only the minimum is needed (D record) the levels are visited
-// by ascending shift, ties by index, so the levels a group of buckets can use form a prefix;
-// when the level itself is tracked the order stays ascending in s (ties go to the smallest s
-// through the strict "<").  Workgroup (l, g) stages layer l for candidates g*64 .. g*64+63.
-__global__ __launch_bounds__(256) void dp_stage_levels(const int32_t *__restrict__ tau,
-                                                       const float *__restrict__ err, int K,
-                                                       int L, int S, int s8, int sorted,
-                                                       LevelPair *__restrict__ pairs)
+// Prepare, workgroup 1 + l: the order in which the fill visits the levels of layer l, and their
+// shifts tau - m_l in that order; padding up to s8 gets shift INT32_MAX, which no group of
+// buckets can use.  When only the minimum is needed (D record) the levels are visited by
+// ascending shift, ties by index, so the levels a group of buckets can use form a prefix; when
+// the level itself is tracked the order stays ascending in s (ties then go to the smallest s
+// through the strict "<").  One thread per level (S <= 255).
+__device__ void prepare_order(const int32_t *__restrict__ tau, int l, int S, int s8, int sorted,
+                              int32_t *__restrict__ shifts, int32_t *__restrict__ order)
 {
-    __shared__ int s_shift[256];
-    __shared__ int s_level[256];
-    const int l = blockIdx.x, tid = threadIdx.x;
-    if (tid < S) {
+    const int s = threadIdx.x;
+    int32_t *shifts_l = shifts + (size_t)l * s8;
+    int32_t *order_l = order + (size_t)l * s8;
+    if (s < S) {
         const int32_t *tau_l = tau + (size_t)l * S;
-        const int mine = tau_l[tid];
+        const int mine = tau_l[s];
         int rank = 0, m = INT32_MAX;
         for (int o = 0; o < S; ++o) {
             const int other = tau_l[o];
             m = min(m, other);
-            rank += (other < mine || (other == mine && o < tid)) ? 1 : 0;
+            rank += (other < mine || (other == mine && o < s)) ? 1 : 0;
         }
         if (!sorted)
-            rank = tid;
-        s_shift[rank] = mine - m;
-        s_level[rank] = tid;
-    }
-    __syncthreads();
-    const int k0 = blockIdx.y * kStageCands;
-    const int nk = min(kStageCands, K - k0);
-    for (int i = tid; i < nk * s8; i += blockDim.x) {
-        const int k = k0 + i / s8, r = i % s8;
-        LevelPair p;
-        p.shift = INT32_MAX;
-        p.err = __builtin_inff();
-        if (r < S) {
-            p.shift = s_shift[r];
-            p.err = err[((size_t)k * L + l) * S + s_level[r]];
-        }
-        pairs[((size_t)k * L + l) * s8 + r] = p;
+            rank = s;
+        shifts_l[rank] = mine - m;
+        order_l[rank] = s;
+    } else if (s < s8) {
+        shifts_l[s] = INT32_MAX;
+        order_l[s] = 0;
     }
 }
 
+__global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ tau, int L, int S,
+                                                  int s8, int B, int waves, int max_group,
+                                                  int lds_small, int lds_large, int sorted,
+                                                  int32_t *__restrict__ meta,
+                                                  int32_t *__restrict__ shifts,
+                                                  int32_t *__restrict__ order)
+{
+    if (blockIdx.x == 0)
+        prepare_budget(tau, L, S, B, waves, max_group, lds_small, lds_large, meta);
+    else
+        prepare_order(tau, blockIdx.x - 1, S, s8, sorted, shifts, order);
+}
+
+// ---------------------------------------------------------------------------------------------
 // v_min_f32 / v_min3_f32 without the canonicalising v_max the compiler puts in front of fminf
 // (no NaN can occur: err is finite or +inf and D starts at -0 / +inf).
 __device__ __forceinline__ void vmin(float &b, float x)
@@ -316,15 +315,24 @@ __device__ __forceinline__ void vmin3(float &b, float x, float y)
     asm("v_min3_f32 %0, %0, %1, %2" : "+v"(b) : "v"(x), "v"(y));
 }
 
-// This lane's entry of the 64 staged levels starting at level `blk` (padding past s8).
-__device__ __forceinline__ LevelPair load_level(const LevelPair *__restrict__ pairs_l, int s8,
-                                                int blk, int lane)
+struct LevelEntry {   // one visited level of one layer of one candidate
+    int32_t shift;    // tau - m_l (INT32_MAX in padding entries)
+    float err;
+};
+
+// This lane's entry of the 64 visited levels of a layer starting at position `blk`.
+__device__ __forceinline__ LevelEntry load_level(const int32_t *__restrict__ shifts_l,
+                                                 const int32_t *__restrict__ order_l,
+                                                 const float *__restrict__ err_kl, int s8, int blk,
+                                                 int lane)
 {
-    LevelPair p;
+    LevelEntry p;
     p.shift = INT32_MAX;
     p.err = __builtin_inff();
-    if (blk + lane < s8)
-        p = pairs_l[blk + lane];
+    if (blk + lane < s8) {
+        p.shift = shifts_l[blk + lane];
+        p.err = err_kl[order_l[blk + lane]];
+    }
     return p;
 }
 
@@ -333,18 +341,19 @@ __device__ __forceinline__ float lane_value(float v, int lane)
     return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), lane));
 }
 
-// Resident path: the levels of one layer swept over one group of R chunks (R*64 consecutive
-// reduced buckets from t0); best[j] / arg[j] belong to bucket t0 + 64*j + lane.
-//   prev    : LDS row of the previous layer, prev[-kHalo .. -1] reads +inf
-//   first   : lane i holds staged level i of the layer (levels 0..63)
-//   pairs_l : the layer's s8 staged levels, sorted by shift unless kLevel (for levels >= 64)
+// The levels of one layer swept over one group of R chunks (R*64 consecutive reduced buckets
+// from t0); best[j] / arg[j] belong to bucket t0 + 64*j + lane.
+//   prev  : row of the previous layer, prev[-kHalo .. -1] reads +inf
+//   first : lane i holds visited level i of the layer (positions 0..63)
+//   shifts_l / order_l / err_kl : the layer's tables, for positions >= 64
 // A level applies to the group if its shift does not exceed the group's last bucket; lanes
 // left of the shift then read the +inf apron.  The applicable levels of a 64-block are found
-// with one ballot and walked in ascending order; shift and error reach the scalar registers
-// with v_readlane, so the sweep issues no memory instruction besides the LDS reads.
+// with one ballot and walked in ascending position.
 template <int R, bool kLevel>
-__device__ __forceinline__ void sweep_group(const float *__restrict__ prev, LevelPair first,
-                                            const LevelPair *__restrict__ pairs_l, int s8, int t0,
+__device__ __forceinline__ void sweep_group(const float *__restrict__ prev, LevelEntry first,
+                                            const int32_t *__restrict__ shifts_l,
+                                            const int32_t *__restrict__ order_l,
+                                            const float *__restrict__ err_kl, int s8, int t0,
                                             int lane, float (&best)[R], unsigned (&arg)[R])
 {
 #pragma unroll
@@ -359,7 +368,8 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, Leve
     };
 
     for (int blk = 0; blk < s8; blk += kWave) {
-        const LevelPair mine = blk == 0 ? first : load_level(pairs_l, s8, blk, lane);
+        const LevelEntry mine =
+            blk == 0 ? first : load_level(shifts_l, order_l, err_kl, s8, blk, lane);
         unsigned long long use = __ballot(mine.shift <= last);
         if constexpr (kLevel) {
             while (use) {
@@ -367,7 +377,7 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, Leve
                 use &= use - 1;
                 const float *p = row_at(__builtin_amdgcn_readlane(mine.shift, i));
                 const float e = lane_value(mine.err, i);
-                const unsigned s = (unsigned)(blk + i);
+                const unsigned s = (unsigned)(blk + i);   // visiting order = level index here
 #pragma unroll
                 for (int j = 0; j < R; ++j) {
                     // strict "<" decides the level; the value is the min either way (the sign
@@ -408,9 +418,10 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, Leve
 // from the first write (every wave of the workgroup calls this exactly once per layer then,
 // with R = 0 if it has no chunks).
 template <int R, bool kLevel, bool inplace>
-__device__ __forceinline__ void fill_group_lds(const float *prev, float *cur, uint8_t *choice,
-                                               float *rec, LevelPair first,
-                                               const LevelPair *pairs_l, int s8, int t0, int lane)
+__device__ __forceinline__ void fill_group(const float *prev, float *cur, uint8_t *choice,
+                                           float *rec, LevelEntry first, const int32_t *shifts_l,
+                                           const int32_t *order_l, const float *err_kl, int s8,
+                                           int t0, int lane)
 {
     if constexpr (R == 0) {
         if (inplace)
@@ -418,7 +429,7 @@ __device__ __forceinline__ void fill_group_lds(const float *prev, float *cur, ui
     } else {
         float best[R];
         unsigned arg[R];
-        sweep_group<R, kLevel>(prev, first, pairs_l, s8, t0, lane, best, arg);
+        sweep_group<R, kLevel>(prev, first, shifts_l, order_l, err_kl, s8, t0, lane, best, arg);
         const int tl = t0 + lane;
 #pragma unroll
         for (int j = 0; j < R; ++j) {
@@ -436,16 +447,16 @@ __device__ __forceinline__ void fill_group_lds(const float *prev, float *cur, ui
 }
 
 template <bool kLevel, bool inplace>
-__device__ __forceinline__ void fill_group_lds_n(int r, const float *prev, float *cur,
-                                                 uint8_t *choice, float *rec, LevelPair first,
-                                                 const LevelPair *pairs_l, int s8, int t0,
-                                                 int lane)
+__device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cur, uint8_t *choice,
+                                             float *rec, LevelEntry first,
+                                             const int32_t *shifts_l, const int32_t *order_l,
+                                             const float *err_kl, int s8, int t0, int lane)
 {
     switch (r) {
 #define SPDY_CASE(RR)                                                                          \
     case RR:                                                                                   \
-        fill_group_lds<RR, kLevel, inplace>(prev, cur, choice, rec, first, pairs_l, s8, t0,    \
-                                            lane);                                             \
+        fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, shifts_l, order_l,      \
+                                        err_kl, s8, t0, lane);                                 \
         break;
         SPDY_CASE(0)
         SPDY_CASE(1)
@@ -462,120 +473,13 @@ __device__ __forceinline__ void fill_group_lds_n(int r, const float *prev, float
 #define SPDY_CASE(RR)                                                                          \
     case RR:                                                                                   \
         if constexpr (!kLevel)                                                                 \
-            fill_group_lds<RR, kLevel, inplace>(prev, cur, choice, rec, first, pairs_l, s8,    \
-                                                t0, lane);                                     \
+            fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, shifts_l, order_l,  \
+                                            err_kl, s8, t0, lane);                             \
         break;
         SPDY_CASE(11)
         SPDY_CASE(12)
         SPDY_CASE(13)
 #undef SPDY_CASE
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Streamed path: one group of R chunks (R*64 consecutive reduced buckets from t0) of one layer,
-// rows in global memory, per-lane bounds test where the group straddles t = shift.
-//   prev / cur : the two D rows (LDS or global)
-//   kLevel     : track the level per cell and store it to `choice` (Alg. 1's P)
-//   kRecord    : also store the value to `rec` (the D record in global memory)
-//   tau_l / err_l : the S times and errors of this layer for this candidate (wave-uniform);
-//   mn         : the layer's smallest time, so the shift of level s is tau_l[s] - mn
-template <int R, bool kLevel, bool kRecord>
-__device__ __forceinline__ void fill_group(const float *__restrict__ prev, float *__restrict__ cur,
-                                           uint8_t *__restrict__ choice, float *__restrict__ rec,
-                                           const int32_t *__restrict__ tau_l, int mn,
-                                           const float *__restrict__ err_l, int S, int t0,
-                                           int lane)
-{
-    float best[R];
-    unsigned arg[R];
-#pragma unroll
-    for (int j = 0; j < R; ++j) {
-        best[j] = __builtin_inff();
-        arg[j] = kNoLevel;
-    }
-    const int tl = t0 + lane;                 // this lane's bucket in chunk 0 of the group
-    const int last = t0 + R * kWave - 1;      // last bucket of the group
-
-    for (int s = 0; s < S; ++s) {
-        const int ts = tau_l[s] - mn;
-        const float es = err_l[s];
-        if (ts > last)
-            continue;                         // every lane would read left of t = 0
-        if (ts <= t0) {                       // every lane reads inside the row
-            const float *p = prev + (tl - ts);
-#pragma unroll
-            for (int j = 0; j < R; ++j) {
-                const float v = p[j * kWave] + es;
-                if constexpr (kLevel) {
-                    if (v < best[j]) {
-                        best[j] = v;
-                        arg[j] = (unsigned)s;
-                    }
-                } else {
-                    best[j] = fminf(best[j], v);
-                }
-            }
-        } else {                              // the group straddles t = tau: test per lane
-#pragma unroll
-            for (int j = 0; j < R; ++j) {
-                const int u = tl + j * kWave - ts;
-                if (u >= 0) {
-                    const float v = prev[u] + es;
-                    if constexpr (kLevel) {
-                        if (v < best[j]) {
-                            best[j] = v;
-                            arg[j] = (unsigned)s;
-                        }
-                    } else {
-                        best[j] = fminf(best[j], v);
-                    }
-                }
-            }
-        }
-    }
-#pragma unroll
-    for (int j = 0; j < R; ++j) {
-        cur[tl + j * kWave] = best[j];
-        if constexpr (kLevel)
-            choice[tl + j * kWave] = (uint8_t)arg[j];
-        if constexpr (kRecord)
-            rec[tl + j * kWave] = best[j];
-    }
-}
-
-// Chunks [c, c_end) of one layer, in groups of at most kMaxGroup chunks of near-equal size.
-template <bool kLevel, bool kRecord>
-__device__ __forceinline__ void fill_chunks(const float *prev, float *cur, uint8_t *choice,
-                                            float *rec, const int32_t *tau_l, int mn,
-                                            const float *err_l, int S, int c, int c_end, int lane)
-{
-    while (c < c_end) {
-        const int n = c_end - c;
-        const int groups = (n + kMaxGroup - 1) / kMaxGroup;
-        const int r = (n + groups - 1) / groups;
-        const int t0 = c * kWave;
-        switch (r) {
-#define SPDY_CASE(RR)                                                                          \
-    case RR:                                                                                   \
-        fill_group<RR, kLevel, kRecord>(prev, cur, choice, rec, tau_l, mn, err_l, S, t0, lane); \
-        break;
-            SPDY_CASE(1)
-            SPDY_CASE(2)
-            SPDY_CASE(3)
-            SPDY_CASE(4)
-            SPDY_CASE(5)
-            SPDY_CASE(6)
-            SPDY_CASE(7)
-            SPDY_CASE(8)
-            SPDY_CASE(9)
-            SPDY_CASE(10)
-            SPDY_CASE(11)
-            SPDY_CASE(12)
-            SPDY_CASE(13)
-#undef SPDY_CASE
-        }
-        c += r;
     }
 }
 
@@ -588,36 +492,6 @@ __device__ __forceinline__ void argmin_merge(float &bv, int &bt, float v, int t)
     }
 }
 
-// Smallest t <= top attaining min_t row[t], reduced over the workgroup.  scratch_v / scratch_t:
-// one word per wave each, in LDS, not aliasing row.  Result valid in thread 0.
-__device__ __forceinline__ void block_argmin(const float *row, int top, float *scratch_v,
-                                             int *scratch_t, float &out_v, int &out_t)
-{
-    const int tid = threadIdx.x, nthreads = blockDim.x;
-    float bv = __builtin_inff();
-    int bt = INT32_MAX;
-    for (int t = tid; t <= top; t += nthreads)
-        argmin_merge(bv, bt, row[t], t);
-#pragma unroll
-    for (int off = kWave / 2; off > 0; off >>= 1) {
-        const float ov = __shfl_down(bv, off, kWave);
-        const int ot = __shfl_down(bt, off, kWave);
-        argmin_merge(bv, bt, ov, ot);
-    }
-    const int wave = tid / kWave, nwaves = nthreads / kWave;
-    if ((tid & (kWave - 1)) == 0) {
-        scratch_v[wave] = bv;
-        scratch_t[wave] = bt;
-    }
-    __syncthreads();
-    if (tid == 0) {
-        for (int w = 1; w < nwaves; ++w)
-            argmin_merge(bv, bt, scratch_v[w], scratch_t[w]);
-        out_v = bv;
-        out_t = bt;
-    }
-}
-
 __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *tstar, float *cost)
 {
     cost[k] = bv;
@@ -625,19 +499,24 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 }
 
 // ---------------------------------------------------------------------------------------------
-// Resident path: the reduced D row(s) of a candidate stay in LDS for all L layers.  The waves of
-// a workgroup form `teams` teams of `tw` waves; team i of workgroup b solves candidate
-// b * teams + i.  Barriers are workgroup-wide, so every team steps through the layers together.
-// In-place mode (every wave holds all its chunks in registers): one row per team; a layer is
-// swept, barrier, written back, barrier.  Otherwise two rows alternate with one barrier a layer.
-// `pitch` is the record's row pitch; the record row of layer l is l + 1 (D) or l (levels).
-template <bool kLevel>
-__global__ __launch_bounds__(kResidentThreads, 8) void dp_fill_resident(
-    const LevelPair *__restrict__ pairs, const int32_t *__restrict__ meta, int path, int K, int L,
-    int s8, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
-    int32_t *__restrict__ tstar, float *__restrict__ cost)
+// The fill (Eq. 2-3 for all L layers) and the final argmin over t.  The waves of a workgroup
+// form `teams` teams of `tw` waves; team i of workgroup b solves candidate b * teams + i.
+// Barriers are workgroup-wide, so every team steps through the layers together.
+//   kLds     : the rows live in LDS (`path` 1 or 2); otherwise in `rows` in global memory
+//              (`path` 0: one candidate per workgroup, two rows of kHalo + pitch floats each)
+//   in place : a layer is swept, barrier, written back to the same row, barrier; otherwise two
+//              rows alternate with one barrier per layer
+// `pitch` is the record's row pitch (elements per (k, l) row).
+template <bool kLevel, bool kLds>
+__global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
+    const float *__restrict__ err, const int32_t *__restrict__ meta,
+    const int32_t *__restrict__ shifts, const int32_t *__restrict__ order, int path, int K, int L,
+    int S, int s8, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
+    float *__restrict__ rows, int32_t *__restrict__ tstar, float *__restrict__ cost)
 {
     extern __shared__ float lds[];
+    __shared__ float s_best[kFillWaves];
+    __shared__ int s_time[kFillWaves];
     if (meta[kMetaPath] != path)
         return;                                  // another launch does the work
     const int bp = meta[kMetaBudget];
@@ -659,27 +538,38 @@ __global__ __launch_bounds__(kResidentThreads, 8) void dp_fill_resident(
     const int wv = wave - team * tw;             // this wave's index in its team
     const int k = blockIdx.x * teams + team;
     const bool active = team < teams && k < K;
-    const int stride = kHalo + row;              // floats per LDS row incl. its apron
+
+    // rows: [apron | row] once (in place) or twice per team
+    const int stride = kHalo + (kLds ? row : pitch);
     const int team_floats = inplace ? stride : 2 * stride;
-    float *buf0 = lds + (size_t)(team < teams ? team : 0) * team_floats + kHalo;
+    float *base = kLds ? lds + (size_t)(team < teams ? team : 0) * team_floats
+                       : rows + (size_t)blockIdx.x * team_floats;
+    float *buf0 = base + kHalo;
     float *buf1 = inplace ? buf0 : buf0 + stride;
 
     // D before the first layer: time 0 costs nothing, nothing else is reachable (Eq. 3 then is
     // the general update).  -0.0f + e returns e bit for bit for every e, +0.0f would not for
     // e = -0.0f.  Aprons and chunks a layer does not compute keep this +inf.
-    for (int i = tid; i < teams * team_floats; i += nthreads)
-        lds[i] = (i % team_floats == kHalo) ? -0.0f : __builtin_inff();
+    if constexpr (kLds) {
+        for (int i = tid; i < teams * team_floats; i += nthreads)
+            lds[i] = (i % team_floats == kHalo) ? -0.0f : __builtin_inff();
+    } else {
+        for (int i = tid; i < team_floats; i += nthreads)
+            if (i % stride < kHalo + row)
+                base[i] = (i == kHalo) ? -0.0f : __builtin_inff();
+    }
     __syncthreads();
 
     const int32_t *nact = meta + kMetaHeader + L;
-    const LevelPair *pairs_k = pairs + (size_t)(active ? k : 0) * L * s8;
+    const float *err_k = err + (size_t)(active ? k : 0) * L * S;
 
-    // lane i keeps staged level i of the layer being swept; the next layer's is fetched early
-    LevelPair next_first = load_level(pairs_k, s8, 0, lane);
+    // lane i keeps visited level i of the layer being swept; the next layer's is fetched early
+    LevelEntry next_first = load_level(shifts, order, err_k, s8, 0, lane);
     for (int l = 0; l < L; ++l) {
-        const LevelPair first = next_first;
+        const LevelEntry first = next_first;
         if (l + 1 < L)
-            next_first = load_level(pairs_k + (size_t)(l + 1) * s8, s8, 0, lane);
+            next_first = load_level(shifts + (size_t)(l + 1) * s8, order + (size_t)(l + 1) * s8,
+                                    err_k + (size_t)(l + 1) * S, s8, 0, lane);
         const float *prev = (l & 1) ? buf1 : buf0;
         float *cur = (l & 1) ? buf0 : buf1;
         int c = 0, c_end = 0;
@@ -689,29 +579,29 @@ __global__ __launch_bounds__(kResidentThreads, 8) void dp_fill_resident(
             c_end = (int)((long long)(wv + 1) * n / tw);
         }
         uint8_t *choice_l = kLevel ? choice + ((size_t)k * L + l) * pitch : nullptr;
-        float *drec_l = kLevel ? nullptr : drec + ((size_t)k * (L + 1) + l + 1) * pitch;
-        const LevelPair *pairs_l = pairs_k + (size_t)l * s8;
+        float *drec_l = kLevel ? nullptr : drec + ((size_t)k * L + l) * pitch;
+        const int32_t *shifts_l = shifts + (size_t)l * s8;
+        const int32_t *order_l = order + (size_t)l * s8;
+        const float *err_kl = err_k + (size_t)l * S;
         constexpr int kMax = kLevel ? kMaxGroupLevel : kMaxGroup;
         if (inplace) {                           // c_end - c <= kMax by construction
-            fill_group_lds_n<kLevel, true>(min(c_end - c, kMax), prev, cur, choice_l, drec_l,
-                                           first, pairs_l, s8, c * kWave, lane);
+            fill_group_n<kLevel, true>(min(c_end - c, kMax), prev, cur, choice_l, drec_l, first,
+                                       shifts_l, order_l, err_kl, s8, c * kWave, lane);
         } else {
             while (c < c_end) {
                 const int n = c_end - c;
                 const int groups = (n + kMax - 1) / kMax;
                 const int r = (n + groups - 1) / groups;
-                fill_group_lds_n<kLevel, false>(r, prev, cur, choice_l, drec_l, first, pairs_l,
-                                                s8, c * kWave, lane);
+                fill_group_n<kLevel, false>(r, prev, cur, choice_l, drec_l, first, shifts_l,
+                                            order_l, err_kl, s8, c * kWave, lane);
                 c += r;
             }
         }
         __syncthreads();
     }
 
-    // final argmin over t' <= bp within each team; the apron (and a second row) is dead now
+    // final argmin over t' <= bp within each team
     const float *last = (L & 1) ? buf1 : buf0;
-    float *scratch_v = ((L & 1) ? buf0 : buf1) - kHalo;
-    int *scratch_t = reinterpret_cast<int *>(scratch_v) + kResidentWaves;
     float bv = __builtin_inff();
     int bt = INT32_MAX;
     if (active)
@@ -723,110 +613,16 @@ __global__ __launch_bounds__(kResidentThreads, 8) void dp_fill_resident(
         const int ot = __shfl_down(bt, off, kWave);
         argmin_merge(bv, bt, ov, ot);
     }
-    if (active && lane == 0) {
-        scratch_v[wv] = bv;
-        scratch_t[wv] = bt;
+    if (lane == 0) {
+        s_best[wave] = bv;
+        s_time[wave] = bt;
     }
     __syncthreads();
     if (active && wv == 0 && lane == 0) {
         for (int w = 1; w < tw; ++w)
-            argmin_merge(bv, bt, scratch_v[w], scratch_t[w]);
+            argmin_merge(bv, bt, s_best[wave + w], s_time[wave + w]);
         write_result(bv, bt, k, tstar, cost);
     }
-}
-
-// ---------------------------------------------------------------------------------------------
-// Streamed path (two reduced rows exceed LDS): D rows live in global memory, one launch per
-// layer.  With the D record the rows ARE the record (layer l reads record row l, writes row
-// l + 1); with the level record two rows per candidate ping-pong.
-
-// Level record: both ping-pong rows start at +inf, D before the first layer has -0.0f at t = 0.
-__global__ void dp_init_rows(const int32_t *__restrict__ meta, float *__restrict__ d0,
-                             float *__restrict__ d1, int pitch, int K)
-{
-    if (meta[kMetaPath] != 0)
-        return;
-    const size_t n = (size_t)K * pitch;
-    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
-         i += (size_t)gridDim.x * blockDim.x) {
-        d0[i] = (i % pitch == 0) ? -0.0f : __builtin_inff();
-        d1[i] = __builtin_inff();
-    }
-}
-
-// D record: row 0 of every candidate is D before the first layer, as far as layer 0 reads it.
-__global__ void dp_init_record(const int32_t *__restrict__ meta, float *__restrict__ drec,
-                               int pitch, int L, int K)
-{
-    if (meta[kMetaPath] != 0)
-        return;
-    const int n0 = meta[kMetaHeader + L] * kWave;    // buckets layer 0 computes
-    for (int k = blockIdx.x; k < K; k += gridDim.x) {
-        float *r = drec + (size_t)k * (L + 1) * pitch;
-        for (int t = threadIdx.x; t < n0; t += blockDim.x)
-            r[t] = (t == 0) ? -0.0f : __builtin_inff();
-    }
-}
-
-template <bool kLevel>
-__global__ __launch_bounds__(kStreamThreads) void dp_layer_streamed(
-    const int32_t *__restrict__ tau, const float *__restrict__ err,
-    const int32_t *__restrict__ meta, int l, int L, int S, int pitch,
-    uint8_t *__restrict__ choice, float *__restrict__ drec, const float *__restrict__ dprev,
-    float *__restrict__ dcur)
-{
-    if (meta[kMetaPath] != 0)
-        return;
-    const int k = blockIdx.x;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x / kWave);
-    const int32_t *nact = meta + kMetaHeader + L;
-    const int n = nact[l];
-    // chunks the next layer may read beyond this layer's reach must hold +inf in the D record
-    const int n_next = kLevel ? n : nact[l + 1 < L ? l + 1 : l];
-    const int c = (blockIdx.y * (kStreamThreads / kWave) + wave) * kStreamGroup;
-    if (c >= n_next)
-        return;
-    const float *prev;
-    float *cur;
-    uint8_t *choice_l = nullptr;
-    if constexpr (kLevel) {
-        prev = dprev + (size_t)k * pitch;
-        cur = dcur + (size_t)k * pitch;
-        choice_l = choice + ((size_t)k * L + l) * pitch;
-    } else {
-        prev = drec + ((size_t)k * (L + 1) + l) * pitch;
-        cur = drec + ((size_t)k * (L + 1) + l + 1) * pitch;
-    }
-    const int c_fill = min(c + kStreamGroup, n);
-    if (c < c_fill)
-        fill_chunks<kLevel, false>(prev, cur, choice_l, nullptr, tau + (size_t)l * S,
-                                   meta[kMetaHeader + l], err + ((size_t)k * L + l) * S, S, c,
-                                   c_fill, lane);
-    if constexpr (!kLevel) {
-        const int c_inf = min(c + kStreamGroup, n_next);
-        for (int cc = max(c, n); cc < c_inf; ++cc)
-            cur[cc * kWave + lane] = __builtin_inff();
-    }
-}
-
-// Final argmin for the streamed path; `stride` separates the candidates' last rows.
-__global__ __launch_bounds__(kStreamThreads) void dp_final_argmin(
-    const int32_t *__restrict__ meta, const float *__restrict__ dlast, size_t stride, int L,
-    int32_t *__restrict__ tstar, float *__restrict__ cost)
-{
-    __shared__ float sv[kStreamThreads / kWave];
-    __shared__ int st[kStreamThreads / kWave];
-    if (meta[kMetaPath] != 0)
-        return;
-    const int k = blockIdx.x;
-    // buckets beyond the last layer's computed chunks are +inf by construction (not stored)
-    const int top = min(meta[kMetaBudget], meta[kMetaHeader + 2 * L - 1] * kWave - 1);
-    float bv;
-    int bt;
-    block_argmin(dlast + (size_t)k * stride, top, sv, st, bv, bt);
-    if (threadIdx.x == 0)
-        write_result(bv, bt, k, tstar, cost);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -882,8 +678,8 @@ __global__ void dp_backtrace_levels(const int32_t *__restrict__ tau, const float
 // D record: one wave per candidate.  At (l, t) the lanes try the levels in parallel: lane s
 // forms D_{l-1}[t - shift_s] + err[l][s] with the same single fp32 add as the fill and compares
 // it with D_l[t]; the lowest matching level is the one a strict "<" sweep would have kept.
-// Only the gather of D_{l-1} depends on t, so the shifts and errors of the next layer down are
-// fetched while that gather is in flight: one memory round trip per layer on the critical path.
+// Only the gather of D_{l-1} depends on t, so it is issued first and the shifts and errors of the
+// next layer down are fetched behind it: one memory round trip per layer on the critical path.
 // The cost is then re-summed over the profile in layer order, which reproduces the sign of a
 // zero exactly as the level-tracking sweep would (min(+0, -0) is order-blind).
 // kLevelBlocks: 64-level blocks a lane holds (1 for S <= 64, 4 for S <= 255).
@@ -916,14 +712,14 @@ __device__ __forceinline__ LayerLevels<kLevelBlocks> load_layer(
 }
 
 template <int kLevelBlocks>
-__global__ __launch_bounds__(kStreamThreads) void dp_backtrace_values(
+__global__ __launch_bounds__(kWalkThreads) void dp_backtrace_values(
     const int32_t *__restrict__ tau, const float *__restrict__ err,
     const int32_t *__restrict__ meta, const float *__restrict__ drec,
     const int32_t *__restrict__ tstar, int K, int L, int S, int pitch,
     int16_t *__restrict__ profile, float *__restrict__ cost)
 {
     const int lane = threadIdx.x & (kWave - 1);
-    const int k = blockIdx.x * (kStreamThreads / kWave) + threadIdx.x / kWave;
+    const int k = blockIdx.x * (kWalkThreads / kWave) + threadIdx.x / kWave;
     if (k >= K)
         return;
     int16_t *prof = profile + (size_t)k * L;
@@ -933,14 +729,14 @@ __global__ __launch_bounds__(kStreamThreads) void dp_backtrace_values(
             prof[l] = -1;
         return;
     }
-    const float *drec_k = drec + (size_t)k * (L + 1) * pitch;
+    const float *drec_k = drec + (size_t)k * L * pitch;
     const float *err_k = err + (size_t)k * L * S;
-    float target = drec_k[(size_t)L * pitch + t];
+    float target = drec_k[(size_t)(L - 1) * pitch + t];
     LayerLevels<kLevelBlocks> next = load_layer<kLevelBlocks>(tau, err_k, meta, L - 1, L, S, lane);
     bool ok = true;
     for (int l = L - 1; l >= 0; --l) {
         const LayerLevels<kLevelBlocks> cur = next;
-        const float *prow = drec_k + (size_t)l * pitch;      // record row l = layer l - 1
+        const float *prow = drec_k + (size_t)(l > 0 ? l - 1 : 0) * pitch;   // row of layer l - 1
         // issue the gather of D_{l-1} first, then the next layer's table behind it
         int u[kLevelBlocks];
         float pv[kLevelBlocks];
@@ -1004,23 +800,24 @@ int launch_status()
 
 template <bool kLevel>
 int launch_fill(const Layout &lay, const int32_t *tau, const float *err, int K, int L, int S,
-                int B, float *cost, char *ws, hipStream_t q)
+                int B, char *ws, float *cost, hipStream_t q)
 {
     int32_t *meta = reinterpret_cast<int32_t *>(ws + lay.meta_off);
+    int32_t *shifts = reinterpret_cast<int32_t *>(ws + lay.shifts_off);
+    int32_t *order = reinterpret_cast<int32_t *>(ws + lay.order_off);
     int32_t *tstar = reinterpret_cast<int32_t *>(ws + lay.tstar_off);
     uint8_t *choice = kLevel ? reinterpret_cast<uint8_t *>(ws + lay.record_off) : nullptr;
     float *drec = kLevel ? nullptr : reinterpret_cast<float *>(ws + lay.record_off);
+    float *rows = reinterpret_cast<float *>(ws + (kLevel ? lay.rows_level : lay.rows_value));
     const int pitch = (int)lay.row;
     const int nchunks = pitch / kWave;
-    const int chunks_per_block = (kStreamThreads / kWave) * kStreamGroup;
-    const int yblocks = (nchunks + chunks_per_block - 1) / chunks_per_block;
-    if ((lay.may_stream && yblocks > 65535) || (K + kStageCands - 1) / kStageCands > 65535)
-        return SPDY_DP_ERR_OVERFLOW;
+    const int s8 = (int)lay.s8;
 
-    // The reduced row length is only known on the device, so the resident kernel is enqueued
-    // with an LDS allocation that lets two workgroups share a compute unit and, if the full
-    // budget could need more, once more with a larger one; the prepare kernel picks the launch
-    // that fits and the other returns at once.
+    // The reduced row length is only known on the device, so the fill kernel is enqueued with an
+    // LDS allocation that lets two workgroups share a compute unit and, if the full budget could
+    // need more, once more with a larger one (and once with the rows in global memory if even
+    // that may not do); the prepare kernel picks the launch that fits and the others return at
+    // once.
     const size_t full_need = 2 * (lay.row + kHalo) * sizeof(float);
     int lds_small, lds_large;
     if (full_need <= (size_t)kLdsHalf) {
@@ -1030,48 +827,26 @@ int launch_fill(const Layout &lay, const int32_t *tau, const float *err, int K, 
         lds_small = kLdsHalf;
         lds_large = full_need <= (size_t)kLdsBytes ? (int)full_need : kLdsBytes;
     }
-    auto resident = dp_fill_resident<kLevel>;
+    auto in_lds = dp_fill<kLevel, true>;
+    auto in_global = dp_fill<kLevel, false>;
     const int lds_max = lds_large ? lds_large : lds_small;
     if (lds_max > 64 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(resident),
+        hipFuncSetAttribute(reinterpret_cast<const void *>(in_lds),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_max) != hipSuccess)
         return SPDY_DP_ERR_LAUNCH;
-    const int waves = nchunks < kResidentWaves ? nchunks : kResidentWaves;
-    LevelPair *pairs = reinterpret_cast<LevelPair *>(ws + lay.pairs_off);
-    const int s8 = (int)lay.s8;
+    const int waves = nchunks < kFillWaves ? nchunks : kFillWaves;
 
-    hipLaunchKernelGGL(dp_prepare, dim3(1), dim3(256), 0, q, tau, L, S, B, waves,
-                       kLevel ? kMaxGroupLevel : kMaxGroup, lds_small, lds_large, meta);
-    hipLaunchKernelGGL(dp_stage_levels, dim3(L, (K + kStageCands - 1) / kStageCands), dim3(256),
-                       0, q, tau, err, K, L, S, s8, kLevel ? 0 : 1, pairs);
-    hipLaunchKernelGGL(resident, dim3(K), dim3(waves * kWave), lds_small, q, pairs, meta, 1, K, L,
-                       s8, pitch, choice, drec, tstar, cost);
+    hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, L, S, s8, B, waves,
+                       kLevel ? kMaxGroupLevel : kMaxGroup, lds_small, lds_large, kLevel ? 0 : 1,
+                       meta, shifts, order);
+    hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_small, q, err, meta, shifts, order,
+                       1, K, L, S, s8, pitch, choice, drec, rows, tstar, cost);
     if (lds_large)
-        hipLaunchKernelGGL(resident, dim3(K), dim3(waves * kWave), lds_large, q, pairs, meta, 2, K,
-                           L, s8, pitch, choice, drec, tstar, cost);
-    if (!lay.may_stream)
-        return launch_status();
-
-    // the reduced rows may still exceed LDS: enqueue the per-layer path as well; each kernel
-    // looks at the prepare kernel's verdict and exactly one of the two paths does the work
-    float *d0 = nullptr, *d1 = nullptr;
-    if constexpr (kLevel) {
-        d0 = reinterpret_cast<float *>(ws + lay.rows_off);
-        d1 = d0 + (size_t)K * lay.row;
-        hipLaunchKernelGGL(dp_init_rows, dim3(1024), dim3(256), 0, q, meta, d0, d1, pitch, K);
-    } else {
-        hipLaunchKernelGGL(dp_init_record, dim3(K < 4096 ? K : 4096), dim3(256), 0, q, meta, drec,
-                           pitch, L, K);
-    }
-    const dim3 grid(K, yblocks);
-    auto layer = dp_layer_streamed<kLevel>;
-    for (int l = 0; l < L; ++l)
-        hipLaunchKernelGGL(layer, grid, dim3(kStreamThreads), 0, q, tau, err, meta, l, L, S, pitch,
-                           choice, drec, (l & 1) ? d1 : d0, (l & 1) ? d0 : d1);
-    const float *dlast = kLevel ? ((L & 1) ? d1 : d0) : drec + (size_t)L * pitch;
-    const size_t stride = kLevel ? (size_t)pitch : ((size_t)L + 1) * pitch;
-    hipLaunchKernelGGL(dp_final_argmin, dim3(K), dim3(kStreamThreads), 0, q, meta, dlast, stride,
-                       L, tstar, cost);
+        hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_large, q, err, meta, shifts,
+                           order, 2, K, L, S, s8, pitch, choice, drec, rows, tstar, cost);
+    if (lay.may_spill)
+        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, err, meta, shifts, order,
+                           0, K, L, S, s8, pitch, choice, drec, rows, tstar, cost);
     return launch_status();
 }
 
@@ -1112,7 +887,7 @@ int spdy_dp_workspace_layout(int K, int L, int S, int B, size_t workspace_bytes,
     out[2] = lay.tstar_off;
     out[3] = lay.record_off;
     out[4] = lay.row;
-    out[5] = lay.variant == kValueRecord ? (size_t)L + 1 : (size_t)L;
+    out[5] = (size_t)L;
     return SPDY_DP_OK;
 }
 
@@ -1129,8 +904,8 @@ int spdy_dp_fill(const int32_t *tau, const float *err, int K, int L, int S, int 
     char *ws = static_cast<char *>(workspace);
     (void)hipGetLastError();
     return lay.variant == kLevelRecord
-               ? launch_fill<true>(lay, tau, err, K, L, S, B, cost, ws, q)
-               : launch_fill<false>(lay, tau, err, K, L, S, B, cost, ws, q);
+               ? launch_fill<true>(lay, tau, err, K, L, S, B, ws, cost, q)
+               : launch_fill<false>(lay, tau, err, K, L, S, B, ws, cost, q);
 }
 
 int spdy_dp_backtrace(const int32_t *tau, const float *err, int K, int L, int S, int B,
@@ -1153,12 +928,11 @@ int spdy_dp_backtrace(const int32_t *tau, const float *err, int K, int L, int S,
                            tau, err, meta, reinterpret_cast<const uint8_t *>(ws + lay.record_off),
                            tstar, K, L, S, (int)lay.row, profile, cost);
     } else {
-        const int per_block = kStreamThreads / kWave;
+        const int per_block = kWalkThreads / kWave;
         hipLaunchKernelGGL(S <= kWave ? dp_backtrace_values<1> : dp_backtrace_values<4>,
-                           dim3((K + per_block - 1) / per_block), dim3(kStreamThreads), 0, q, tau,
-                           err, meta,
-                           reinterpret_cast<const float *>(ws + lay.record_off), tstar, K, L, S,
-                           (int)lay.row, profile, cost);
+                           dim3((K + per_block - 1) / per_block), dim3(kWalkThreads), 0, q, tau,
+                           err, meta, reinterpret_cast<const float *>(ws + lay.record_off), tstar,
+                           K, L, S, (int)lay.row, profile, cost);
     }
     return launch_status();
 }

@@ -56,23 +56,24 @@ def test_workspace_size(binding):
     fast = binding.spdy_dp_workspace_bytes(K, L, S, B)
     small = binding.spdy_dp_workspace_bytes_min(K, L, S, B)
     # fp32 D per cell (one extra row per candidate) vs one byte per cell, rows padded to 64
-    staged = 8 * K * L * ((S + 7) // 8 * 8)     # (shift, err) pair per (candidate, layer, level)
-    assert 4 * K * (L + 1) * row + staged <= fast <= 4 * K * (L + 1) * row + staged + 16384
-    assert K * L * row + staged <= small <= K * L * row + staged + 16384
+    tables = 2 * 4 * L * ((S + 7) // 8 * 8)     # visiting order and shifts per (layer, level)
+    assert 4 * K * L * row + tables <= fast <= 4 * K * L * row + tables + 16384
+    assert K * L * row + tables <= small <= K * L * row + tables + 16384
     lay = binding.spdy_dp_workspace_layout(K, L, S, B, fast)
-    assert lay["variant"] == 0 and lay["record_pitch"] == row and lay["record_rows"] == L + 1
+    assert lay["variant"] == 0 and lay["record_pitch"] == row and lay["record_rows"] == L
     lay = binding.spdy_dp_workspace_layout(K, L, S, B, fast - 1)
     assert lay["variant"] == 1 and lay["record_pitch"] == row and lay["record_rows"] == L
     assert lay["record_offset"] % 256 == 0 and lay["tstar_offset"] % 256 == 0
-    assert lay["tstar_offset"] >= 4 * (8 + 2 * L)
-    assert lay["record_offset"] >= lay["tstar_offset"] + 4 * K + staged
+    assert lay["tstar_offset"] >= 4 * (8 + 2 * L) + tables
+    assert lay["record_offset"] >= lay["tstar_offset"] + 4 * K
     with pytest.raises(binding.SpdyDpError) as e:
         binding.spdy_dp_workspace_layout(K, L, S, B, small - 1)
     assert e.value.status == binding.ERR_WORKSPACE
-    # rows that do not fit LDS add two fp32 rows per candidate to the level-record variant
+    # rows that may not fit LDS add two fp32 rows per candidate
     K, L, S, B = 256, 200, 64, 65536
     row = (B + 1 + 63) // 64 * 64
     assert binding.spdy_dp_workspace_bytes_min(K, L, S, B) >= K * L * row + 2 * K * row * 4
+    assert binding.spdy_dp_workspace_bytes(K, L, S, B) >= 4 * K * L * row + 2 * K * row * 4
     # invalid sizes -> 0
     for f in (binding.spdy_dp_workspace_bytes, binding.spdy_dp_workspace_bytes_min):
         assert f(0, 1, 1, 1) == 0

@@ -83,14 +83,14 @@ def check_tables(dp, tau, err_k, B, ws, k, K):
     a = lay["record_offset"] + k * rows * pitch * esize
     rec = ws[a:a + rows * pitch * esize].cpu().numpy()
     rec = rec.view(np.float32 if esize == 4 else np.uint8).reshape(rows, pitch)
-    if meta[3] == 0:     # per-layer kernels ran: the reduced rows (plus aprons) exceed LDS
-        assert 2 * (meta[2] + 832) * 4 > 160 * 1024
+    if meta[3] == 0:     # rows in global memory: the reduced rows (plus aprons) exceed LDS
+        assert 2 * (meta[2] + 832) * 4 > 160 * 1024 - 256
     for l in range(L):
         n = int(min(nact[l] * 64, bp + 1))
         want_D = D[l, lo[l]:lo[l] + n]
         assert np.isinf(D[l, lo[l] + n:lo[l] + bp + 1]).all(), f"layer {l}: reach bound wrong"
         if lay["variant"] == 0:
-            got = rec[l + 1, :n]
+            got = rec[l, :n]
             assert (got == want_D).all(), f"layer {l}: D record differs"
         else:
             fin = np.isfinite(want_D)
@@ -134,7 +134,7 @@ EDGE_SHAPES = [
     # K, L, S, B  (B + 1 deliberately not a multiple of 64 in most; several chunks per wave)
     (3, 1, 1, 0), (2, 1, 5, 7), (4, 5, 1, 100), (5, 6, 7, 63), (5, 6, 7, 64), (3, 9, 12, 1000),
     (7, 12, 33, 2500), (2, 4, 255, 700), (3, 17, 40, 10000), (2, 20, 16, 16384),
-    (2, 7, 9, 20478), (2, 6, 10, 20479),             # largest rows that still fit LDS
+    (2, 7, 9, 19583), (2, 6, 10, 19584),             # around the largest rows that fit LDS
     (3, 6, 10, 20480), (2, 5, 12, 33000), (1, 4, 6, 70001),   # rows in global memory
 ]
 
