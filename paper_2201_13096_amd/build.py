@@ -9,11 +9,13 @@ _ROOT = os.path.dirname(_HERE)
 SOURCE = os.path.join(_HERE, "csrc", "spdy_dp.hip")
 INCLUDE = os.path.join(_ROOT, "include")
 LIB_PATH = os.path.join(_HERE, "libspdy_dp.so")
+PROBE_SOURCE = os.path.join(_HERE, "csrc", "peaks_probe.hip")
+PROBE_PATH = os.path.join(_HERE, "peaks_probe")
 
 # packed-fp32 instructions are switched off on purpose (every fp32 op is an ordinary
 # v_add_f32 / v_cmp / v_cndmask); subnormals stay on (the default for fp32 on gfx9).
 HIPCC_FLAGS = [
-    "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC", "-shared",
+    "-O3", "--offload-arch=gfx950", "-std=c++17", "-fPIC",
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
     "-fno-fast-math", "-ffp-contract=off", "-fno-gpu-flush-denormals-to-zero",
     "-Wall", "-Wextra",
@@ -23,7 +25,7 @@ HIPCC_FLAGS = [
 def build_library(verbose: bool = False) -> str:
     """Always recompiles; returns the path of the shared library."""
     tmp = LIB_PATH + f".tmp{os.getpid()}"
-    cmd = ["hipcc", *HIPCC_FLAGS, f"-I{INCLUDE}", SOURCE, "-o", tmp]
+    cmd = ["hipcc", *HIPCC_FLAGS, "-shared", f"-I{INCLUDE}", SOURCE, "-o", tmp]
     res = subprocess.run(cmd, capture_output=True, text=True)
     if res.returncode != 0:
         raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stdout + res.stderr)
@@ -33,5 +35,17 @@ def build_library(verbose: bool = False) -> str:
     return LIB_PATH
 
 
+def build_probe() -> str:
+    """Compile the stand-alone VALU / LDS rate probe (an executable, run by hand on the GPU)."""
+    tmp = PROBE_PATH + f".tmp{os.getpid()}"
+    cmd = ["hipcc", *HIPCC_FLAGS, PROBE_SOURCE, "-o", tmp]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("hipcc failed:\n" + " ".join(cmd) + "\n" + res.stdout + res.stderr)
+    os.replace(tmp, PROBE_PATH)
+    return PROBE_PATH
+
+
 if __name__ == "__main__":
     print(build_library(verbose=True))
+    print(build_probe())
