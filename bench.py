@@ -31,6 +31,9 @@ LANE_OPS_PER_UPDATE = {"d": 2, "level": 4}
 # unit for 32-bit reads (64 lanes in two clocks).
 LDS_PEAK_BYTES = 256 * 128 * 2.4e9
 LDS_BYTES_PER_UPDATE = 4
+# HBM bytes per launch of the fill kernel, from FETCH_SIZE / WRITE_SIZE counter runs scaled by a
+# plain copy of known size (profiles/dp_fill_rn50_k1024_*.md).  None where not measured.
+MEASURED_TRAFFIC_BYTES = {("rn50_k1024", "d"): 957e6, ("rn50_k1024", "level"): 246e6}
 
 
 def executed_updates_per_candidate(tau: np.ndarray, B: int) -> int:
@@ -154,7 +157,8 @@ def main() -> int:
             "frac": achieved / ALU_PEAK_LANE_OPS,
             "lane_ops_per_update": ops,
             "kernel_ms": fill_ms,
-            "traffic": None,
+            "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, args.record))
+            if K == cfg.K else None,
         },
         "roofline_lds": {
             "achieved": lds_achieved / 1e12,
