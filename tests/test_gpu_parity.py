@@ -136,6 +136,9 @@ EDGE_SHAPES = [
     (7, 12, 33, 2500), (2, 4, 255, 700), (3, 17, 40, 10000), (2, 20, 16, 16384),
     (2, 7, 9, 19583), (2, 6, 10, 19584),             # around the largest rows that fit LDS
     (3, 6, 10, 20480), (2, 5, 12, 33000), (1, 4, 6, 70001),   # rows in global memory
+    (2, 300, 3, 500),                                # more layers than prepare threads
+    (2, 5, 64, 300), (2, 5, 65, 300), (3, 4, 129, 900),       # level-block boundaries
+    (37, 4, 5, 200), (19, 3, 6, 1500),               # candidates not a multiple of the teams
 ]
 
 
@@ -144,7 +147,7 @@ def test_random_tables_bit_exact(dp, shape):
     K, L, S, B = shape
     print(f"[parity] random tables K={K} L={L} S={S} B={B}", flush=True)
     rng = np.random.default_rng(K * 1000003 + L * 10007 + S * 101 + B)
-    for variant in range(5):
+    for variant in range(7):
         kw = dict(tau_max=max(1, B // max(1, L // 2)))
         if variant == 1:
             kw.update(integer_err=3)                        # ties everywhere
@@ -154,6 +157,10 @@ def test_random_tables_bit_exact(dp, shape):
             kw.update(integer_err=2, zero_tau_frac=0.3, tau_max=max(1, B // (2 * L) + 1))
         elif variant == 4:   # large per-layer floors: the reduced budget is a fraction of B
             kw.update(integer_err=4, tau_max=max(1, B // (2 * L)), layer_floor=B // L)
+        elif variant == 5:   # errors in the fp32 subnormal range, some times at the int32 limit
+            kw.update(err_scale=2.0 ** -140, huge_tau_frac=0.1)
+        elif variant == 6:   # subnormal integers: ties and subnormals together
+            kw.update(integer_err=5, err_scale=2.0 ** -149, zero_tau_frac=0.1)
         tau, err, _ = workloads.random_instance(rng, K, L, S, B, **kw)
         p_ref, c_ref = oracle.solve_ref(tau, err, B)
         for compact in (False, True):

@@ -95,14 +95,17 @@ def generate(cfg: Config, seed: int = 0, K: int | None = None):
 def random_instance(rng: np.random.Generator, K: int, L: int, S: int, B: int, *,
                     tau_max: int | None = None, integer_err: int | None = None,
                     zero_tau_frac: float = 0.0, over_budget_frac: float = 0.0,
-                    inf_err_frac: float = 0.0, layer_floor: int = 0):
+                    inf_err_frac: float = 0.0, layer_floor: int = 0, huge_tau_frac: float = 0.0,
+                    err_scale: float = 1.0):
     """Unstructured random tables for tests (no monotonicity in s, Sec. 3.1: timings are
     non-linear and a sparse layer can be slower than the dense one).
 
     ``integer_err=m`` draws errors from {0..m-1} (sums exact in fp32, ties frequent); otherwise
     errors are uniform in [0, 1).  Fractions select entries forced to tau = 0, tau > B, err = +inf.
     ``layer_floor > 0`` adds a random per-layer offset in [0, layer_floor] to every time of the
-    layer, so that the smallest time of a layer is well above zero.
+    layer, so that the smallest time of a layer is well above zero.  ``huge_tau_frac`` forces
+    entries to the largest int32; ``err_scale`` multiplies every error (a power of two far below
+    one moves the errors into the fp32 subnormal range).
     """
     tau_max = max(1, B // 2) if tau_max is None else tau_max
     tau = rng.integers(0, tau_max + 1, size=(L, S), dtype=np.int64)
@@ -113,10 +116,14 @@ def random_instance(rng: np.random.Generator, K: int, L: int, S: int, B: int, *,
     if over_budget_frac > 0:
         m = rng.random((L, S)) < over_budget_frac
         tau[m] = B + 1 + rng.integers(0, 5, size=int(m.sum()))
+    if huge_tau_frac > 0:
+        tau[rng.random((L, S)) < huge_tau_frac] = 2 ** 31 - 1
     if integer_err is not None:
         err = rng.integers(0, integer_err, size=(K, L, S)).astype(np.float32)
     else:
         err = rng.random((K, L, S), dtype=np.float32)
+    if err_scale != 1.0:
+        err = (err * np.float32(err_scale)).astype(np.float32)
     if inf_err_frac > 0:
         err[rng.random((K, L, S)) < inf_err_frac] = np.inf
     return np.ascontiguousarray(tau.astype(np.int32)), np.ascontiguousarray(err), B
