@@ -103,6 +103,18 @@ int spdy_dp_backtrace(const int32_t *tau, const float *err, int K, int L, int S,
                       int16_t *profile, float *cost, const void *workspace,
                       size_t workspace_bytes, void *stream);
 
+/* spdy_dp_solve_batched for error tables of the form of Eq. 4: err[k][l][s] = c[k][l] * w[s],
+ * a per-layer sensitivity times a fixed per-level weight (Eq. 4: w_i = (i / (S - 1))^2).  The
+ * product is formed on the device with one round-to-nearest fp32 multiply wherever an error is
+ * needed, so the K * L * S table never exists in memory; results equal spdy_dp_solve_batched on
+ * the table err = fl32(c * w), bit for bit.
+ *   c  in  fp32 [K][L]  sensitivities, finite (inf * 0 would be NaN)
+ *   w  in  fp32 [S]     level weights, finite
+ * Workspace, outputs and status codes as for spdy_dp_solve_batched. */
+int spdy_dp_solve_sensitivities(const int32_t *tau, const float *c, const float *w, int K, int L,
+                                int S, int B, int16_t *profile, float *cost, void *workspace,
+                                size_t workspace_bytes, void *stream);
+
 /* Test/debug accessor: where things are in a workspace of `workspace_bytes` bytes.
  *   out[0] variant: 0 = fp32 D record, 1 = one-byte level record
  *   out[1] byte offset of the int32 header: [0] B - M (or -1 if M > B: nobody is feasible),

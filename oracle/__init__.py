@@ -49,6 +49,9 @@ def _load():
         lib.spdy_dp_solve_ref.restype = ctypes.c_int
         lib.spdy_dp_solve_ref.argtypes = [i32p, f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                           ctypes.c_int, i16p, f32p]
+        lib.spdy_dp_solve_sens_ref.restype = ctypes.c_int
+        lib.spdy_dp_solve_sens_ref.argtypes = [i32p, f32p, f32p, ctypes.c_int, ctypes.c_int,
+                                               ctypes.c_int, ctypes.c_int, i16p, f32p]
         lib.spdy_dp_tables_ref.restype = ctypes.c_int
         lib.spdy_dp_tables_ref.argtypes = [i32p, f32p, ctypes.c_int, ctypes.c_int, ctypes.c_int,
                                            f32p, i32p, i16p, f32p]
@@ -109,6 +112,26 @@ def solve_ref(tau, err, B: int, threads: int = 1):
         if st != 0:
             raise ValueError(f"spdy_dp_solve_ref failed with status {st}")
     return (np.concatenate([p for _, p, _ in parts]), np.concatenate([c for _, _, c in parts]))
+
+
+def solve_sens_ref(tau, c, w, B: int):
+    """Alg. 1 on err[k,l,s] = fl32(c[k,l] * w[s]) (Eq. 4).  Returns ``(profile, cost)``."""
+    tau = np.ascontiguousarray(tau, dtype=np.int32)
+    c = np.ascontiguousarray(c, dtype=np.float32)
+    w = np.ascontiguousarray(w, dtype=np.float32)
+    if tau.ndim != 2 or c.ndim != 2 or w.ndim != 1 or c.shape[1] != tau.shape[0] \
+            or w.shape[0] != tau.shape[1]:
+        raise ValueError("tau [L, S], c [K, L], w [S] expected")
+    K, L = c.shape
+    S = w.shape[0]
+    profile = np.full((K, L), -2, dtype=np.int16)
+    cost = np.full((K,), np.nan, dtype=np.float32)
+    st = _load().spdy_dp_solve_sens_ref(_ptr(tau, ctypes.c_int32), _ptr(c, ctypes.c_float),
+                                        _ptr(w, ctypes.c_float), K, L, S, int(B),
+                                        _ptr(profile, ctypes.c_int16), _ptr(cost, ctypes.c_float))
+    if st != 0:
+        raise ValueError(f"spdy_dp_solve_sens_ref failed with status {st}")
+    return profile, cost
 
 
 def tables_ref(tau, err, B: int):

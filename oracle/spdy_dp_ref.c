@@ -152,6 +152,32 @@ int spdy_dp_solve_ref(const int32_t *tau, const float *err, int K, int L, int S,
     return REF_OK;
 }
 
+/* Error tables of the form of Eq. 4: err[k][l][s] = c[k][l] * w[s] (sensitivity of the layer times
+ * a fixed weight of the level), each product ONE rounded fp32 multiply; then Alg. 1 as above.
+ * c fp32[K][L], w fp32[S], both finite. */
+int spdy_dp_solve_sens_ref(const int32_t *tau, const float *c, const float *w, int K, int L, int S,
+                           int B, int16_t *profile, float *cost)
+{
+    if (!tau || !c || !w || !profile || !cost)
+        return REF_ERR_NULL;
+    if (K <= 0 || L <= 0 || S <= 0 || B < 0)
+        return REF_ERR_DIM;
+    float *e = (float *)malloc((size_t)L * S * sizeof(float));
+    if (!e)
+        return REF_ERR_NOMEM;
+    int st = REF_OK;
+    for (int k = 0; k < K && st == REF_OK; ++k) {
+        for (int l = 0; l < L; ++l)
+            for (int s = 0; s < S; ++s) {
+                const float prod = c[(size_t)k * L + l] * w[s];
+                e[(size_t)l * S + s] = prod;
+            }
+        st = spdy_dp_solve_ref(tau, e, 1, L, S, B, profile + (size_t)k * L, cost + k);
+    }
+    free(e);
+    return st;
+}
+
 /* Same as above for ONE candidate, also handing back the full matrices (caller-allocated,
  * D fp32[L][B+1], P int32[L][B+1] with -1 where no level was chosen). */
 int spdy_dp_tables_ref(const int32_t *tau, const float *err, int L, int S, int B, float *D,

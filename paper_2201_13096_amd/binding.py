@@ -18,7 +18,8 @@ OK = 0
 ERR_NULL, ERR_DIM, ERR_LEVELS, ERR_WORKSPACE, ERR_OVERFLOW, ERR_LAUNCH = -1, -2, -3, -4, -5, -9
 
 EXPORTS = ("spdy_dp_workspace_bytes", "spdy_dp_workspace_bytes_min", "spdy_dp_solve_batched",
-           "spdy_dp_fill", "spdy_dp_backtrace", "spdy_dp_workspace_layout", "spdy_dp_strerror")
+           "spdy_dp_solve_sensitivities", "spdy_dp_fill", "spdy_dp_backtrace",
+           "spdy_dp_workspace_layout", "spdy_dp_strerror")
 
 
 class SpdyDpError(RuntimeError):
@@ -43,6 +44,8 @@ def lib() -> ctypes.CDLL:
         L.spdy_dp_workspace_bytes_min.argtypes = [i, i, i, i]
         L.spdy_dp_solve_batched.restype = i
         L.spdy_dp_solve_batched.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, sz, vp]
+        L.spdy_dp_solve_sensitivities.restype = i
+        L.spdy_dp_solve_sensitivities.argtypes = [vp, vp, vp, i, i, i, i, vp, vp, vp, sz, vp]
         L.spdy_dp_fill.restype = i
         L.spdy_dp_fill.argtypes = [vp, vp, i, i, i, i, vp, vp, sz, vp]
         L.spdy_dp_backtrace.restype = i
@@ -127,6 +130,34 @@ def spdy_dp_solve_batched(tau, err, B: int, profile=None, cost=None, workspace=N
     st = lib().spdy_dp_solve_batched(tau.data_ptr(), err.data_ptr(), K, L, S, int(B),
                                      profile.data_ptr(), cost.data_ptr(), workspace.data_ptr(),
                                      workspace.numel(), _stream(stream))
+    if st != OK:
+        raise SpdyDpError(st)
+    return profile, cost
+
+
+def spdy_dp_solve_sensitivities(tau, c, w, B: int, profile=None, cost=None, workspace=None,
+                                stream=None):
+    """Alg. 1 for err[k,l,s] = c[k,l] * w[s] (Eq. 4) without materialising the table."""
+    tau = _dev(tau, torch.int32, "tau")
+    c = _dev(c, torch.float32, "c")
+    w = _dev(w, torch.float32, "w")
+    if tau.dim() != 2 or c.dim() != 2 or w.dim() != 1 or c.shape[1] != tau.shape[0] \
+            or w.shape[0] != tau.shape[1]:
+        raise ValueError("tau must be [L, S], c [K, L] and w [S]")
+    K, L, S = int(c.shape[0]), int(tau.shape[0]), int(tau.shape[1])
+    if profile is None:
+        profile = torch.empty((K, L), dtype=torch.int16, device=c.device)
+    if cost is None:
+        cost = torch.empty((K,), dtype=torch.float32, device=c.device)
+    if workspace is None:
+        workspace = alloc_workspace(K, L, S, B, c.device)
+    _dev(profile, torch.int16, "profile")
+    _dev(cost, torch.float32, "cost")
+    _dev(workspace, torch.uint8, "workspace")
+    st = lib().spdy_dp_solve_sensitivities(tau.data_ptr(), c.data_ptr(), w.data_ptr(), K, L, S,
+                                           int(B), profile.data_ptr(), cost.data_ptr(),
+                                           workspace.data_ptr(), workspace.numel(),
+                                           _stream(stream))
     if st != OK:
         raise SpdyDpError(st)
     return profile, cost

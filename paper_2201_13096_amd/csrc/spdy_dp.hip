@@ -315,6 +315,31 @@ __device__ __forceinline__ void vmin3(float &b, float x, float y)
     asm("v_min3_f32 %0, %0, %1, %2" : "+v"(b) : "v"(x), "v"(y));
 }
 
+// Where err[k][l][s] comes from: an explicit table, or the product of a per-layer sensitivity
+// c[k][l] and a per-level weight w[s] (Eq. 4), formed with one fp32 multiply when it is needed.
+struct ErrRow {          // the S errors of one (candidate, layer)
+    const float *err_kl; // explicit row, or nullptr
+    const float *w;
+    float c_kl;
+    __device__ __forceinline__ float at(int s) const
+    {
+        return err_kl ? err_kl[s] : __fmul_rn(c_kl, w[s]);
+    }
+};
+struct ErrSource {
+    const float *err;    // [K][L][S], or nullptr
+    const float *c;      // [K][L]
+    const float *w;      // [S]
+    __device__ __forceinline__ ErrRow row(size_t k, int l, int L, int S) const
+    {
+        ErrRow r;
+        r.err_kl = err ? err + (k * L + l) * S : nullptr;
+        r.w = w;
+        r.c_kl = err ? 0.0f : c[k * L + l];
+        return r;
+    }
+};
+
 struct LevelEntry {   // one visited level of one layer of one candidate
     int32_t shift;    // tau - m_l (INT32_MAX in padding entries)
     float err;
@@ -323,15 +348,14 @@ struct LevelEntry {   // one visited level of one layer of one candidate
 // This lane's entry of the 64 visited levels of a layer starting at position `blk`.
 __device__ __forceinline__ LevelEntry load_level(const int32_t *__restrict__ shifts_l,
                                                  const int32_t *__restrict__ order_l,
-                                                 const float *__restrict__ err_kl, int s8, int blk,
-                                                 int lane)
+                                                 ErrRow er, int s8, int blk, int lane)
 {
     LevelEntry p;
     p.shift = INT32_MAX;
     p.err = __builtin_inff();
     if (blk + lane < s8) {
         p.shift = shifts_l[blk + lane];
-        p.err = err_kl[order_l[blk + lane]];
+        p.err = er.at(order_l[blk + lane]);
     }
     return p;
 }
@@ -345,7 +369,7 @@ __device__ __forceinline__ float lane_value(float v, int lane)
 // from t0); best[j] / arg[j] belong to bucket t0 + 64*j + lane.
 //   prev  : row of the previous layer, prev[-kHalo .. -1] reads +inf
 //   first : lane i holds visited level i of the layer (positions 0..63)
-//   shifts_l / order_l / err_kl : the layer's tables, for positions >= 64
+//   shifts_l / order_l / er : the layer's tables, for positions >= 64
 // A level applies to the group if its shift does not exceed the group's last bucket; lanes
 // left of the shift then read the +inf apron.  The applicable levels of a 64-block are found
 // with one ballot and walked in ascending position.
@@ -353,8 +377,8 @@ template <int R, bool kLevel>
 __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, LevelEntry first,
                                             const int32_t *__restrict__ shifts_l,
                                             const int32_t *__restrict__ order_l,
-                                            const float *__restrict__ err_kl, int s8, int t0,
-                                            int lane, float (&best)[R], unsigned (&arg)[R])
+                                            ErrRow er, int s8, int t0, int lane,
+                                            float (&best)[R], unsigned (&arg)[R])
 {
 #pragma unroll
     for (int j = 0; j < R; ++j) {
@@ -369,7 +393,7 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, Leve
 
     for (int blk = 0; blk < s8; blk += kWave) {
         const LevelEntry mine =
-            blk == 0 ? first : load_level(shifts_l, order_l, err_kl, s8, blk, lane);
+            blk == 0 ? first : load_level(shifts_l, order_l, er, s8, blk, lane);
         unsigned long long use = __ballot(mine.shift <= last);
         if constexpr (kLevel) {
             while (use) {
@@ -420,8 +444,8 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, Leve
 template <int R, bool kLevel, bool inplace>
 __device__ __forceinline__ void fill_group(const float *prev, float *cur, uint8_t *choice,
                                            float *rec, LevelEntry first, const int32_t *shifts_l,
-                                           const int32_t *order_l, const float *err_kl, int s8,
-                                           int t0, int lane)
+                                           const int32_t *order_l, ErrRow er, int s8, int t0,
+                                           int lane)
 {
     if constexpr (R == 0) {
         if (inplace)
@@ -429,7 +453,7 @@ __device__ __forceinline__ void fill_group(const float *prev, float *cur, uint8_
     } else {
         float best[R];
         unsigned arg[R];
-        sweep_group<R, kLevel>(prev, first, shifts_l, order_l, err_kl, s8, t0, lane, best, arg);
+        sweep_group<R, kLevel>(prev, first, shifts_l, order_l, er, s8, t0, lane, best, arg);
         const int tl = t0 + lane;
 #pragma unroll
         for (int j = 0; j < R; ++j) {
@@ -450,13 +474,13 @@ template <bool kLevel, bool inplace>
 __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cur, uint8_t *choice,
                                              float *rec, LevelEntry first,
                                              const int32_t *shifts_l, const int32_t *order_l,
-                                             const float *err_kl, int s8, int t0, int lane)
+                                             ErrRow er, int s8, int t0, int lane)
 {
     switch (r) {
 #define SPDY_CASE(RR)                                                                          \
     case RR:                                                                                   \
         fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, shifts_l, order_l,      \
-                                        err_kl, s8, t0, lane);                                 \
+                                        er, s8, t0, lane);                                     \
         break;
         SPDY_CASE(0)
         SPDY_CASE(1)
@@ -474,7 +498,7 @@ __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cu
     case RR:                                                                                   \
         if constexpr (!kLevel)                                                                 \
             fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, shifts_l, order_l,  \
-                                            err_kl, s8, t0, lane);                             \
+                                            er, s8, t0, lane);                                 \
         break;
         SPDY_CASE(11)
         SPDY_CASE(12)
@@ -509,8 +533,8 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 // `pitch` is the record's row pitch (elements per (k, l) row).
 template <bool kLevel, bool kLds>
 __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
-    const float *__restrict__ err, const int32_t *__restrict__ meta,
-    const int32_t *__restrict__ shifts, const int32_t *__restrict__ order, int path, int K, int L,
+    ErrSource src, const int32_t *__restrict__ meta, const int32_t *__restrict__ shifts,
+    const int32_t *__restrict__ order, int path, int K, int L,
     int S, int s8, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
     float *__restrict__ rows, int32_t *__restrict__ tstar, float *__restrict__ cost)
 {
@@ -561,15 +585,15 @@ __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
     __syncthreads();
 
     const int32_t *nact = meta + kMetaHeader + L;
-    const float *err_k = err + (size_t)(active ? k : 0) * L * S;
+    const size_t ke = active ? k : 0;            // candidate whose errors this wave reads
 
     // lane i keeps visited level i of the layer being swept; the next layer's is fetched early
-    LevelEntry next_first = load_level(shifts, order, err_k, s8, 0, lane);
+    LevelEntry next_first = load_level(shifts, order, src.row(ke, 0, L, S), s8, 0, lane);
     for (int l = 0; l < L; ++l) {
         const LevelEntry first = next_first;
         if (l + 1 < L)
             next_first = load_level(shifts + (size_t)(l + 1) * s8, order + (size_t)(l + 1) * s8,
-                                    err_k + (size_t)(l + 1) * S, s8, 0, lane);
+                                    src.row(ke, l + 1, L, S), s8, 0, lane);
         const float *prev = (l & 1) ? buf1 : buf0;
         float *cur = (l & 1) ? buf0 : buf1;
         int c = 0, c_end = 0;
@@ -582,18 +606,18 @@ __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
         float *drec_l = kLevel ? nullptr : drec + ((size_t)k * L + l) * pitch;
         const int32_t *shifts_l = shifts + (size_t)l * s8;
         const int32_t *order_l = order + (size_t)l * s8;
-        const float *err_kl = err_k + (size_t)l * S;
+        const ErrRow er = src.row(ke, l, L, S);
         constexpr int kMax = kLevel ? kMaxGroupLevel : kMaxGroup;
         if (inplace) {                           // c_end - c <= kMax by construction
             fill_group_n<kLevel, true>(min(c_end - c, kMax), prev, cur, choice_l, drec_l, first,
-                                       shifts_l, order_l, err_kl, s8, c * kWave, lane);
+                                       shifts_l, order_l, er, s8, c * kWave, lane);
         } else {
             while (c < c_end) {
                 const int n = c_end - c;
                 const int groups = (n + kMax - 1) / kMax;
                 const int r = (n + groups - 1) / groups;
                 fill_group_n<kLevel, false>(r, prev, cur, choice_l, drec_l, first, shifts_l,
-                                            order_l, err_kl, s8, c * kWave, lane);
+                                            order_l, er, s8, c * kWave, lane);
                 c += r;
             }
         }
@@ -630,7 +654,7 @@ __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
 
 // Level record: one lane per candidate, L dependent one-byte reads; the cost is re-summed over
 // the profile in layer order (exactly the sum Alg. 1's strict "<" sweep carries to the cell).
-__global__ void dp_backtrace_levels(const int32_t *__restrict__ tau, const float *__restrict__ err,
+__global__ void dp_backtrace_levels(const int32_t *__restrict__ tau, ErrSource src,
                                     const int32_t *__restrict__ meta,
                                     const uint8_t *__restrict__ choice,
                                     const int32_t *__restrict__ tstar, int K, int L, int S,
@@ -668,10 +692,9 @@ __global__ void dp_backtrace_levels(const int32_t *__restrict__ tau, const float
         return;
     }
     __threadfence();
-    const float *err_k = err + (size_t)k * L * S;
     float acc = -0.0f;
     for (int l = 0; l < L; ++l)
-        acc += err_k[(size_t)l * S + prof[l]];
+        acc += src.row(k, l, L, S).at(prof[l]);
     cost[k] = acc;
 }
 
@@ -692,8 +715,8 @@ struct LayerLevels {
 
 template <int kLevelBlocks>
 __device__ __forceinline__ LayerLevels<kLevelBlocks> load_layer(
-    const int32_t *__restrict__ tau, const float *__restrict__ err_k,
-    const int32_t *__restrict__ meta, int l, int L, int S, int lane)
+    const int32_t *__restrict__ tau, ErrRow er, const int32_t *__restrict__ meta, int l, int L,
+    int S, int lane)
 {
     LayerLevels<kLevelBlocks> v;
     const int m = meta[kMetaHeader + l];
@@ -705,7 +728,7 @@ __device__ __forceinline__ LayerLevels<kLevelBlocks> load_layer(
         v.err[b] = __builtin_inff();
         if (s < S) {
             v.shift[b] = tau[(size_t)l * S + s] - m;
-            v.err[b] = err_k[(size_t)l * S + s];
+            v.err[b] = er.at(s);
         }
     }
     return v;
@@ -713,8 +736,8 @@ __device__ __forceinline__ LayerLevels<kLevelBlocks> load_layer(
 
 template <int kLevelBlocks>
 __global__ __launch_bounds__(kWalkThreads) void dp_backtrace_values(
-    const int32_t *__restrict__ tau, const float *__restrict__ err,
-    const int32_t *__restrict__ meta, const float *__restrict__ drec,
+    const int32_t *__restrict__ tau, ErrSource src, const int32_t *__restrict__ meta,
+    const float *__restrict__ drec,
     const int32_t *__restrict__ tstar, int K, int L, int S, int pitch,
     int16_t *__restrict__ profile, float *__restrict__ cost)
 {
@@ -730,9 +753,9 @@ __global__ __launch_bounds__(kWalkThreads) void dp_backtrace_values(
         return;
     }
     const float *drec_k = drec + (size_t)k * L * pitch;
-    const float *err_k = err + (size_t)k * L * S;
     float target = drec_k[(size_t)(L - 1) * pitch + t];
-    LayerLevels<kLevelBlocks> next = load_layer<kLevelBlocks>(tau, err_k, meta, L - 1, L, S, lane);
+    LayerLevels<kLevelBlocks> next =
+        load_layer<kLevelBlocks>(tau, src.row(k, L - 1, L, S), meta, L - 1, L, S, lane);
     bool ok = true;
     for (int l = L - 1; l >= 0; --l) {
         const LayerLevels<kLevelBlocks> cur = next;
@@ -751,7 +774,7 @@ __global__ __launch_bounds__(kWalkThreads) void dp_backtrace_values(
                 pv[b] = l > 0 ? prow[u[b]] : -0.0f;
         }
         if (l > 0)
-            next = load_layer<kLevelBlocks>(tau, err_k, meta, l - 1, L, S, lane);
+            next = load_layer<kLevelBlocks>(tau, src.row(k, l - 1, L, S), meta, l - 1, L, S, lane);
         int found = -1, next_t = 0;
         float next_target = 0.0f;
 #pragma unroll
@@ -788,7 +811,7 @@ __global__ __launch_bounds__(kWalkThreads) void dp_backtrace_values(
     if (lane == 0) {
         float acc = -0.0f;
         for (int l = 0; l < L; ++l)
-            acc += err_k[(size_t)l * S + prof[l]];
+            acc += src.row(k, l, L, S).at(prof[l]);
         cost[k] = acc;
     }
 }
@@ -799,7 +822,7 @@ int launch_status()
 }
 
 template <bool kLevel>
-int launch_fill(const Layout &lay, const int32_t *tau, const float *err, int K, int L, int S,
+int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, int K, int L, int S,
                 int B, char *ws, float *cost, hipStream_t q)
 {
     int32_t *meta = reinterpret_cast<int32_t *>(ws + lay.meta_off);
@@ -839,13 +862,13 @@ int launch_fill(const Layout &lay, const int32_t *tau, const float *err, int K, 
     hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, L, S, s8, B, waves,
                        kLevel ? kMaxGroupLevel : kMaxGroup, lds_small, lds_large, kLevel ? 0 : 1,
                        meta, shifts, order);
-    hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_small, q, err, meta, shifts, order,
+    hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, shifts, order,
                        1, K, L, S, s8, pitch, choice, drec, rows, tstar, cost);
     if (lds_large)
-        hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_large, q, err, meta, shifts,
+        hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, shifts,
                            order, 2, K, L, S, s8, pitch, choice, drec, rows, tstar, cost);
     if (lay.may_spill)
-        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, err, meta, shifts, order,
+        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, src, meta, shifts, order,
                            0, K, L, S, s8, pitch, choice, drec, rows, tstar, cost);
     return launch_status();
 }
@@ -857,6 +880,63 @@ int validate(const Layout &lay, const void *workspace)
     if (!workspace)
         return SPDY_DP_ERR_NULL;
     return SPDY_DP_OK;
+}
+
+int fill_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B, float *cost,
+              void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!tau || !cost)
+        return SPDY_DP_ERR_NULL;
+    const Layout lay = make_layout(K, L, S, B, workspace_bytes);
+    const int st = validate(lay, workspace);
+    if (st != SPDY_DP_OK)
+        return st;
+    hipStream_t q = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    (void)hipGetLastError();
+    return lay.variant == kLevelRecord
+               ? launch_fill<true>(lay, tau, src, K, L, S, B, ws, cost, q)
+               : launch_fill<false>(lay, tau, src, K, L, S, B, ws, cost, q);
+}
+
+int backtrace_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B,
+                   int16_t *profile, float *cost, const void *workspace, size_t workspace_bytes,
+                   void *stream)
+{
+    if (!tau || !profile || !cost)
+        return SPDY_DP_ERR_NULL;
+    const Layout lay = make_layout(K, L, S, B, workspace_bytes);
+    const int st = validate(lay, workspace);
+    if (st != SPDY_DP_OK)
+        return st;
+    hipStream_t q = static_cast<hipStream_t>(stream);
+    const char *ws = static_cast<const char *>(workspace);
+    const int32_t *meta = reinterpret_cast<const int32_t *>(ws + lay.meta_off);
+    const int32_t *tstar = reinterpret_cast<const int32_t *>(ws + lay.tstar_off);
+    (void)hipGetLastError();
+    if (lay.variant == kLevelRecord) {
+        hipLaunchKernelGGL(dp_backtrace_levels, dim3((K + kWave - 1) / kWave), dim3(kWave), 0, q,
+                           tau, src, meta, reinterpret_cast<const uint8_t *>(ws + lay.record_off),
+                           tstar, K, L, S, (int)lay.row, profile, cost);
+    } else {
+        const int per_block = kWalkThreads / kWave;
+        hipLaunchKernelGGL(S <= kWave ? dp_backtrace_values<1> : dp_backtrace_values<4>,
+                           dim3((K + per_block - 1) / per_block), dim3(kWalkThreads), 0, q, tau,
+                           src, meta, reinterpret_cast<const float *>(ws + lay.record_off), tstar,
+                           K, L, S, (int)lay.row, profile, cost);
+    }
+    return launch_status();
+}
+
+int solve_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B, int16_t *profile,
+               float *cost, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!tau || !profile || !cost)
+        return SPDY_DP_ERR_NULL;
+    const int st = fill_impl(tau, src, K, L, S, B, cost, workspace, workspace_bytes, stream);
+    if (st != SPDY_DP_OK)
+        return st;
+    return backtrace_impl(tau, src, K, L, S, B, profile, cost, workspace, workspace_bytes, stream);
 }
 
 }  // namespace
@@ -894,60 +974,40 @@ int spdy_dp_workspace_layout(int K, int L, int S, int B, size_t workspace_bytes,
 int spdy_dp_fill(const int32_t *tau, const float *err, int K, int L, int S, int B, float *cost,
                  void *workspace, size_t workspace_bytes, void *stream)
 {
-    if (!tau || !err || !cost)
+    if (!err)
         return SPDY_DP_ERR_NULL;
-    const Layout lay = make_layout(K, L, S, B, workspace_bytes);
-    const int st = validate(lay, workspace);
-    if (st != SPDY_DP_OK)
-        return st;
-    hipStream_t q = static_cast<hipStream_t>(stream);
-    char *ws = static_cast<char *>(workspace);
-    (void)hipGetLastError();
-    return lay.variant == kLevelRecord
-               ? launch_fill<true>(lay, tau, err, K, L, S, B, ws, cost, q)
-               : launch_fill<false>(lay, tau, err, K, L, S, B, ws, cost, q);
+    return fill_impl(tau, ErrSource{err, nullptr, nullptr}, K, L, S, B, cost, workspace,
+                     workspace_bytes, stream);
 }
 
 int spdy_dp_backtrace(const int32_t *tau, const float *err, int K, int L, int S, int B,
                       int16_t *profile, float *cost, const void *workspace,
                       size_t workspace_bytes, void *stream)
 {
-    if (!tau || !err || !profile || !cost)
+    if (!err)
         return SPDY_DP_ERR_NULL;
-    const Layout lay = make_layout(K, L, S, B, workspace_bytes);
-    const int st = validate(lay, workspace);
-    if (st != SPDY_DP_OK)
-        return st;
-    hipStream_t q = static_cast<hipStream_t>(stream);
-    const char *ws = static_cast<const char *>(workspace);
-    const int32_t *meta = reinterpret_cast<const int32_t *>(ws + lay.meta_off);
-    const int32_t *tstar = reinterpret_cast<const int32_t *>(ws + lay.tstar_off);
-    (void)hipGetLastError();
-    if (lay.variant == kLevelRecord) {
-        hipLaunchKernelGGL(dp_backtrace_levels, dim3((K + kWave - 1) / kWave), dim3(kWave), 0, q,
-                           tau, err, meta, reinterpret_cast<const uint8_t *>(ws + lay.record_off),
-                           tstar, K, L, S, (int)lay.row, profile, cost);
-    } else {
-        const int per_block = kWalkThreads / kWave;
-        hipLaunchKernelGGL(S <= kWave ? dp_backtrace_values<1> : dp_backtrace_values<4>,
-                           dim3((K + per_block - 1) / per_block), dim3(kWalkThreads), 0, q, tau,
-                           err, meta, reinterpret_cast<const float *>(ws + lay.record_off), tstar,
-                           K, L, S, (int)lay.row, profile, cost);
-    }
-    return launch_status();
+    return backtrace_impl(tau, ErrSource{err, nullptr, nullptr}, K, L, S, B, profile, cost,
+                          workspace, workspace_bytes, stream);
 }
 
 int spdy_dp_solve_batched(const int32_t *tau, const float *err, int K, int L, int S, int B,
                           int16_t *profile, float *cost, void *workspace, size_t workspace_bytes,
                           void *stream)
 {
-    if (!tau || !err || !profile || !cost)
+    if (!err)
         return SPDY_DP_ERR_NULL;
-    const int st = spdy_dp_fill(tau, err, K, L, S, B, cost, workspace, workspace_bytes, stream);
-    if (st != SPDY_DP_OK)
-        return st;
-    return spdy_dp_backtrace(tau, err, K, L, S, B, profile, cost, workspace, workspace_bytes,
-                             stream);
+    return solve_impl(tau, ErrSource{err, nullptr, nullptr}, K, L, S, B, profile, cost, workspace,
+                      workspace_bytes, stream);
+}
+
+int spdy_dp_solve_sensitivities(const int32_t *tau, const float *c, const float *w, int K, int L,
+                                int S, int B, int16_t *profile, float *cost, void *workspace,
+                                size_t workspace_bytes, void *stream)
+{
+    if (!c || !w)
+        return SPDY_DP_ERR_NULL;
+    return solve_impl(tau, ErrSource{nullptr, c, w}, K, L, S, B, profile, cost, workspace,
+                      workspace_bytes, stream);
 }
 
 const char *spdy_dp_strerror(int status)

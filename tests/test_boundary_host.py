@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_function(binding):
     names = declared_functions()
-    assert len(names) >= 7
+    assert len(names) >= 8
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -100,6 +100,11 @@ def test_argument_errors_are_reported_before_any_launch(binding):
     assert solve(fake, fake, 1, 1, 1, 1, fake, fake, fake, 8, None) == binding.ERR_WORKSPACE
     assert solve(fake, fake, 2 ** 31 - 1, 2 ** 31 - 1, 2, 2 ** 31 - 2000, fake, fake, fake,
                  1 << 20, None) == binding.ERR_OVERFLOW
+    sens = lib.spdy_dp_solve_sensitivities
+    assert sens(fake, None, fake, 1, 1, 1, 1, fake, fake, fake, 1 << 20, None) == binding.ERR_NULL
+    assert sens(fake, fake, None, 1, 1, 1, 1, fake, fake, fake, 1 << 20, None) == binding.ERR_NULL
+    assert sens(fake, fake, fake, 1, 1, 300, 1, fake, fake, fake, 1 << 20, None) == \
+        binding.ERR_LEVELS
     assert lib.spdy_dp_fill(fake, fake, 1, 1, 1, 1, None, fake, 1 << 20, None) == binding.ERR_NULL
     bt = lib.spdy_dp_backtrace
     assert bt(fake, fake, 1, 1, 1, 1, None, fake, fake, 1 << 20, None) == binding.ERR_NULL

@@ -105,7 +105,8 @@ def check_tables(dp, tau, err_k, B, ws, k, K):
 
 # --------------------------------------------------------------------------- the five configs
 @pytest.mark.parametrize("compact", [False, True], ids=["d_record", "level_record"])
-@pytest.mark.parametrize("name", ["tiny", "rn50_k1", "rn50_k1024", "bert_k4096", "stress_k256"])
+@pytest.mark.parametrize("name", ["tiny", "rn50_k1", "rn50_k1024", "bert_k4096", "stress_k256",
+                                  "paper_rn50_k1024"])
 def test_config_bit_exact(dp, name, compact, reference):
     cfg = workloads.CONFIGS[name]
     print(f"[parity] config {name}: K={cfg.K} L={cfg.L} S={cfg.S} B={cfg.B} "
@@ -215,6 +216,33 @@ def test_stages_equal_the_fused_call_and_streams(dp):
     assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, "staged, side stream")
     p2, c2, _ = gpu_solve(dp, tau, err, B)
     assert_same(p2, c2, p_ref, c_ref, "fused")
+
+
+@pytest.mark.parametrize("compact", [False, True], ids=["d_record", "level_record"])
+def test_sensitivity_form_bit_exact(dp, compact):
+    """err = c_l * w_s formed on the device (Eq. 4) against the oracle's fused routine."""
+    dev = torch.device("cuda:0")
+    cases = []
+    cfg = workloads.CONFIGS["paper_rn50_k1024"]
+    tau, _, B = workloads.generate(cfg, K=1)
+    rng = np.random.default_rng(5)
+    w = np.square(np.arange(cfg.S, dtype=np.float64) / (cfg.S - 1)).astype(np.float32)
+    cases.append((tau, rng.random((96, cfg.L), dtype=np.float32), w, B))
+    for (K, L, S, B) in [(3, 4, 5, 90), (5, 9, 70, 1200), (2, 6, 130, 22000)]:
+        tau, _, _ = workloads.random_instance(rng, 1, L, S, B, tau_max=max(1, B // L))
+        cases.append((tau, rng.random((K, L), dtype=np.float32),
+                      rng.random(S, dtype=np.float32), B))
+    for tau, c, w, B in cases:
+        K, L = c.shape
+        S = w.shape[0]
+        print(f"[parity] sensitivities K={K} L={L} S={S} B={B} compact={compact}", flush=True)
+        ws = dp.alloc_workspace(K, L, S, B, dev, compact=compact)
+        profile, cost = dp.spdy_dp_solve_sensitivities(
+            torch.from_numpy(tau).to(dev), torch.from_numpy(c).to(dev),
+            torch.from_numpy(w).to(dev), B, workspace=ws)
+        torch.cuda.synchronize()
+        p_ref, c_ref = oracle.solve_sens_ref(tau, c, w, B)
+        assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, "sensitivities")
 
 
 def test_workspace_too_small_is_an_error(dp):

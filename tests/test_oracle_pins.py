@@ -279,7 +279,7 @@ def test_integer_program_cross_check():
 
 
 # --------------------------------------------------------------------------- invariants
-@pytest.mark.parametrize("name", ["tiny", "rn50_k1"])
+@pytest.mark.parametrize("name", ["tiny", "rn50_k1", "paper_rn50_k1024"])
 def test_invariants_on_benchmark_shaped_tables(name):
     cfg = workloads.CONFIGS[name]
     tau, err, B = workloads.generate(cfg, K=3)
@@ -354,6 +354,29 @@ def test_subnormal_errors_are_kept():
     assert c[0] == tiny and c[0] > 0
     p, c = oracle.solve_ref(tau, err, 0)
     assert c[0] == F32(2) * tiny and p[0].tolist() == [1, 1]
+
+
+def test_sensitivity_form_equals_the_explicit_table():
+    """Eq. 4: err = c_l * w_s.  The fused routine must equal Alg. 1 on the table NumPy forms with
+    its own fp32 multiply (one rounding of the exact product), including products that round."""
+    rng = np.random.default_rng(12)
+    for _ in range(30):
+        K, L, S = int(rng.integers(1, 4)), int(rng.integers(1, 7)), int(rng.integers(2, 9))
+        B = int(rng.integers(5, 80))
+        tau, _, _ = workloads.random_instance(rng, 1, L, S, B, tau_max=25)
+        c = rng.random((K, L), dtype=np.float32)
+        w = np.square(np.arange(S, dtype=np.float64) / (S - 1)).astype(np.float32)   # Eq. 4
+        err = (c[:, :, None] * w[None, None, :]).astype(np.float32)
+        assert (err != (c[:, :, None].astype(np.float64) * w).astype(np.float32)).sum() == 0
+        p1, c1 = oracle.solve_sens_ref(tau, c, w, B)
+        p2, c2 = oracle.solve_ref(tau, err, B)
+        assert (p1 == p2).all() and c1.tobytes() == c2.tobytes()
+    # a product that is inexact in fp32 and would differ if it were kept in double
+    tau = np.array([[1, 0]], dtype=np.int32)
+    c = np.array([[F32(1) / F32(3)]], dtype=np.float32)
+    w = np.array([F32(0.1), F32(0.7)], dtype=np.float32)
+    p, cost = oracle.solve_sens_ref(tau, c, w, 0)
+    assert cost[0].tobytes() == F32(c[0, 0] * w[1]).tobytes() and p[0, 0] == 1
 
 
 # --------------------------------------------------------------------------- argument checks

@@ -38,6 +38,7 @@ class Config:
     speedup: float    # X
     dense: str        # how the dense layer times d_l are drawn
     sigma: float      # log-normal sigma of d_l (jitter sigma for "bert")
+    grid: str = "geometric"   # "geometric": p_s = 1 - q**s;  "paper": the Sec. 4 "Setup" grid
 
     @property
     def cell_updates(self) -> int:
@@ -55,12 +56,40 @@ CONFIGS = {
                          dense="bert", sigma=0.1),
     "stress_k256": Config("stress_k256", K=256, L=200, S=64, B=65536, q=0.93, speedup=4.0,
                           dense="lognormal", sigma=1.0),
+    # the sizes Sec. 3.2 quotes for a ResNet-50 (L = 52, |S| = 42, T = 10^4) with the sparsity
+    # grid of Sec. 4 "Setup", the error model of Eq. 4 and non-monotone timings (Sec. 3.1)
+    "paper_rn50_k1024": Config("paper_rn50_k1024", K=1024, L=52, S=42, B=10000, q=0.0,
+                               speedup=2.5, dense="lognormal", sigma=0.8, grid="paper"),
 }
 
 
 def level_grid(S: int, q: float) -> np.ndarray:
     """Sparsity of level s: p_s = 1 - q**s (float64)."""
     return 1.0 - np.power(q, np.arange(S, dtype=np.float64))
+
+
+def paper_grid() -> np.ndarray:
+    """Sec. 4 "Setup": S = {0} u {1 - (1 - 0.4) d^i, i = 0..40}, d = ((1-0.99)/(1-0.4))^(1/40)."""
+    d = ((1.0 - 0.99) / (1.0 - 0.4)) ** (1.0 / 40.0)
+    return np.concatenate([[0.0], 1.0 - 0.6 * np.power(d, np.arange(41, dtype=np.float64))])
+
+
+def _generate_paper_shape(cfg: Config, rng, K: int):
+    """Paper-shaped tables: the Sec. 4 grid (dense + 41 levels from 40 % to 99 % sparsity); sparse
+    execution only pays off from about 40 % sparsity (time factor 0.1 + 1.35 (1-p)^0.9, 0.95 at
+    p = 0.4) and every (layer, level) time carries 5 % log-normal measurement noise, so times are
+    not monotone in the level (Sec. 3.1); errors follow Eq. 4: c_l (i / (|S| - 1))^2."""
+    p = paper_grid()
+    assert cfg.S == p.size
+    d = rng.lognormal(0.0, cfg.sigma, size=cfg.L)
+    f = np.where(p > 0, 0.1 + 1.35 * np.power(1.0 - p, 0.9), 1.0)
+    noise = rng.lognormal(0.0, 0.05, size=(cfg.L, cfg.S))
+    scale = cfg.speedup * cfg.B / d.sum()
+    tau = np.floor(d[:, None] * f[None, :] * noise * scale + 0.5).astype(np.int32)
+    c = rng.random((K, cfg.L))
+    w = np.square(np.arange(cfg.S, dtype=np.float64) / (cfg.S - 1))
+    err = (c[:, :, None] * w[None, None, :]).astype(np.float32)
+    return np.ascontiguousarray(tau), np.ascontiguousarray(err), cfg.B
 
 
 def generate(cfg: Config, seed: int = 0, K: int | None = None):
@@ -71,6 +100,8 @@ def generate(cfg: Config, seed: int = 0, K: int | None = None):
     """
     K = cfg.K if K is None else int(K)
     rng = np.random.Generator(np.random.PCG64(seed))
+    if cfg.grid == "paper":
+        return _generate_paper_shape(cfg, rng, K)
     if cfg.dense == "lognormal":
         d = rng.lognormal(0.0, cfg.sigma, size=cfg.L)
     elif cfg.dense == "bert":
