@@ -115,6 +115,20 @@ int spdy_dp_solve_sensitivities(const int32_t *tau, const float *c, const float 
                                 int S, int B, int16_t *profile, float *cost, void *workspace,
                                 size_t workspace_bytes, void *stream);
 
+/* Several budgets from one fill.  D_l[t] is the least error at EXACTLY time t (Eq. 2-3), so the
+ * table does not depend on the budget: it is filled once for max_j budgets[j], and for every
+ * budget the final argmin runs over t <= budgets[j] and the levels are walked back from there
+ * (profiles for a range of speed-up targets at the cost of one fill).  Results equal J separate
+ * spdy_dp_solve_batched calls, bit for bit.
+ *   budgets  in  int32 [J]        HOST pointer, each >= 0
+ *   profile  out int16 [J][K][L]  device
+ *   cost     out fp32  [J][K]     device
+ * The workspace must have at least spdy_dp_workspace_bytes(K, L, S, max budget) bytes (the D
+ * record keeps the last row the argmin needs); a smaller one returns SPDY_DP_ERR_WORKSPACE. */
+int spdy_dp_solve_budgets(const int32_t *tau, const float *err, int K, int L, int S,
+                          const int32_t *budgets, int J, int16_t *profile, float *cost,
+                          void *workspace, size_t workspace_bytes, void *stream);
+
 /* Test/debug accessor: where things are in a workspace of `workspace_bytes` bytes.
  *   out[0] variant: 0 = fp32 D record, 1 = one-byte level record
  *   out[1] byte offset of the int32 header: [0] B - M (or -1 if M > B: nobody is feasible),

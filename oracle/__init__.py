@@ -134,6 +134,12 @@ def solve_sens_ref(tau, c, w, B: int):
     return profile, cost
 
 
+def solve_budgets_ref(tau, err, budgets, threads: int = 1):
+    """Alg. 1 solved separately for every budget: ``(profile int16[J,K,L], cost fp32[J,K])``."""
+    out = [solve_ref(tau, err, int(b), threads=threads) for b in budgets]
+    return np.stack([p for p, _ in out]), np.stack([c for _, c in out])
+
+
 def tables_ref(tau, err, B: int):
     """Alg. 1 for one candidate, returning ``(D fp32[L,B+1], P int32[L,B+1], profile, cost)``."""
     tau, err = _check(tau, err)

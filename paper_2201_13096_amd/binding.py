@@ -18,7 +18,8 @@ OK = 0
 ERR_NULL, ERR_DIM, ERR_LEVELS, ERR_WORKSPACE, ERR_OVERFLOW, ERR_LAUNCH = -1, -2, -3, -4, -5, -9
 
 EXPORTS = ("spdy_dp_workspace_bytes", "spdy_dp_workspace_bytes_min", "spdy_dp_solve_batched",
-           "spdy_dp_solve_sensitivities", "spdy_dp_fill", "spdy_dp_backtrace",
+           "spdy_dp_solve_sensitivities", "spdy_dp_solve_budgets", "spdy_dp_fill",
+           "spdy_dp_backtrace",
            "spdy_dp_workspace_layout", "spdy_dp_strerror")
 
 
@@ -46,6 +47,9 @@ def lib() -> ctypes.CDLL:
         L.spdy_dp_solve_batched.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, sz, vp]
         L.spdy_dp_solve_sensitivities.restype = i
         L.spdy_dp_solve_sensitivities.argtypes = [vp, vp, vp, i, i, i, i, vp, vp, vp, sz, vp]
+        L.spdy_dp_solve_budgets.restype = i
+        L.spdy_dp_solve_budgets.argtypes = [vp, vp, i, i, i, ctypes.POINTER(ctypes.c_int32), i, vp,
+                                            vp, vp, sz, vp]
         L.spdy_dp_fill.restype = i
         L.spdy_dp_fill.argtypes = [vp, vp, i, i, i, i, vp, vp, sz, vp]
         L.spdy_dp_backtrace.restype = i
@@ -158,6 +162,35 @@ def spdy_dp_solve_sensitivities(tau, c, w, B: int, profile=None, cost=None, work
                                            int(B), profile.data_ptr(), cost.data_ptr(),
                                            workspace.data_ptr(), workspace.numel(),
                                            _stream(stream))
+    if st != OK:
+        raise SpdyDpError(st)
+    return profile, cost
+
+
+def spdy_dp_solve_budgets(tau, err, budgets, profile=None, cost=None, workspace=None,
+                          stream=None):
+    """One fill for max(budgets), then argmin and walk back per budget.  Returns
+    ``(profile int16[J,K,L], cost fp32[J,K])``."""
+    tau = _dev(tau, torch.int32, "tau")
+    err = _dev(err, torch.float32, "err")
+    K, L, S = _shapes(tau, err)
+    budgets = [int(b) for b in budgets]
+    J = len(budgets)
+    if J == 0:
+        raise ValueError("at least one budget")
+    arr = (ctypes.c_int32 * J)(*budgets)
+    if profile is None:
+        profile = torch.empty((J, K, L), dtype=torch.int16, device=err.device)
+    if cost is None:
+        cost = torch.empty((J, K), dtype=torch.float32, device=err.device)
+    if workspace is None:
+        workspace = alloc_workspace(K, L, S, max(budgets), err.device)
+    _dev(profile, torch.int16, "profile")
+    _dev(cost, torch.float32, "cost")
+    _dev(workspace, torch.uint8, "workspace")
+    st = lib().spdy_dp_solve_budgets(tau.data_ptr(), err.data_ptr(), K, L, S, arr, J,
+                                     profile.data_ptr(), cost.data_ptr(), workspace.data_ptr(),
+                                     workspace.numel(), _stream(stream))
     if st != OK:
         raise SpdyDpError(st)
     return profile, cost

@@ -649,6 +649,51 @@ __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
     }
 }
 
+// Final argmin for another budget on an already filled D record: the rows hold exact-time costs
+// and do not depend on the budget, so a smaller budget only shortens the range of the argmin
+// (Sec. 3.2: the answer is min over t <= T of the last row).  One workgroup per candidate.
+__global__ __launch_bounds__(256) void dp_budget_argmin(const int32_t *__restrict__ meta,
+                                                        const float *__restrict__ drec, int L,
+                                                        int pitch, int budget,
+                                                        int32_t *__restrict__ tstar,
+                                                        float *__restrict__ cost)
+{
+    __shared__ float s_best[4];
+    __shared__ int s_time[4];
+    const int k = blockIdx.x, tid = threadIdx.x;
+    const int bp = meta[kMetaBudget];
+    // reduced budget: t' <= budget - M, and never beyond what the fill computed
+    const long long reduced = (long long)budget - meta[kMetaMinTime];
+    long long top = reduced < bp ? reduced : bp;
+    if (bp >= 0) {
+        const long long computed = (long long)meta[kMetaHeader + 2 * L - 1] * kWave - 1;
+        top = top < computed ? top : computed;
+    }
+    float bv = __builtin_inff();
+    int bt = INT32_MAX;
+    if (bp >= 0) {
+        const float *last = drec + ((size_t)k * L + (L - 1)) * pitch;
+        for (int t = tid; t <= top; t += blockDim.x)
+            argmin_merge(bv, bt, last[t], t);
+    }
+#pragma unroll
+    for (int off = kWave / 2; off > 0; off >>= 1) {
+        const float ov = __shfl_down(bv, off, kWave);
+        const int ot = __shfl_down(bt, off, kWave);
+        argmin_merge(bv, bt, ov, ot);
+    }
+    if ((tid & (kWave - 1)) == 0) {
+        s_best[tid / kWave] = bv;
+        s_time[tid / kWave] = bt;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        for (int w = 1; w < 4; ++w)
+            argmin_merge(bv, bt, s_best[w], s_time[w]);
+        write_result(bv, bt, k, tstar, cost);
+    }
+}
+
 // ---------------------------------------------------------------------------------------------
 // Walk back (last loop of Alg. 1).
 
@@ -939,6 +984,47 @@ int solve_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B, in
     return backtrace_impl(tau, src, K, L, S, B, profile, cost, workspace, workspace_bytes, stream);
 }
 
+int budgets_impl(const int32_t *tau, ErrSource src, int K, int L, int S, const int32_t *budgets,
+                 int J, int16_t *profile, float *cost, void *workspace, size_t workspace_bytes,
+                 void *stream)
+{
+    if (!tau || !budgets || !profile || !cost)
+        return SPDY_DP_ERR_NULL;
+    if (J <= 0)
+        return SPDY_DP_ERR_DIM;
+    int bmax = budgets[0];
+    for (int j = 0; j < J; ++j) {
+        if (budgets[j] < 0)
+            return SPDY_DP_ERR_DIM;
+        bmax = budgets[j] > bmax ? budgets[j] : bmax;
+    }
+    const Layout lay = make_layout(K, L, S, bmax, workspace_bytes);
+    int st = validate(lay, workspace);
+    if (st != SPDY_DP_OK)
+        return st;
+    if (lay.variant != kValueRecord)
+        return SPDY_DP_ERR_WORKSPACE;            // the last row of D is only kept in the D record
+    // one fill for the largest budget (cost[0..K) is scratch until its own walk back)
+    st = fill_impl(tau, src, K, L, S, bmax, cost, workspace, workspace_bytes, stream);
+    if (st != SPDY_DP_OK)
+        return st;
+    hipStream_t q = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    const int32_t *meta = reinterpret_cast<const int32_t *>(ws + lay.meta_off);
+    int32_t *tstar = reinterpret_cast<int32_t *>(ws + lay.tstar_off);
+    const float *drec = reinterpret_cast<const float *>(ws + lay.record_off);
+    for (int j = 0; j < J; ++j) {
+        float *cost_j = cost + (size_t)j * K;
+        hipLaunchKernelGGL(dp_budget_argmin, dim3(K), dim3(256), 0, q, meta, drec, L, (int)lay.row,
+                           budgets[j], tstar, cost_j);
+        st = backtrace_impl(tau, src, K, L, S, bmax, profile + (size_t)j * K * L, cost_j,
+                            workspace, workspace_bytes, stream);
+        if (st != SPDY_DP_OK)
+            return st;
+    }
+    return SPDY_DP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1008,6 +1094,16 @@ int spdy_dp_solve_sensitivities(const int32_t *tau, const float *c, const float 
         return SPDY_DP_ERR_NULL;
     return solve_impl(tau, ErrSource{nullptr, c, w}, K, L, S, B, profile, cost, workspace,
                       workspace_bytes, stream);
+}
+
+int spdy_dp_solve_budgets(const int32_t *tau, const float *err, int K, int L, int S,
+                          const int32_t *budgets, int J, int16_t *profile, float *cost,
+                          void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!err)
+        return SPDY_DP_ERR_NULL;
+    return budgets_impl(tau, ErrSource{err, nullptr, nullptr}, K, L, S, budgets, J, profile, cost,
+                        workspace, workspace_bytes, stream);
 }
 
 const char *spdy_dp_strerror(int status)

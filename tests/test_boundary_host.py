@@ -28,7 +28,7 @@ def declared_functions():
 
 def test_library_exports_every_declared_function(binding):
     names = declared_functions()
-    assert len(names) >= 8
+    assert len(names) >= 9
     lib = ctypes.CDLL(binding.LIB_PATH)
     for n in names:
         assert hasattr(lib, n), n
@@ -100,6 +100,13 @@ def test_argument_errors_are_reported_before_any_launch(binding):
     assert solve(fake, fake, 1, 1, 1, 1, fake, fake, fake, 8, None) == binding.ERR_WORKSPACE
     assert solve(fake, fake, 2 ** 31 - 1, 2 ** 31 - 1, 2, 2 ** 31 - 2000, fake, fake, fake,
                  1 << 20, None) == binding.ERR_OVERFLOW
+    one = (ctypes.c_int32 * 2)(5, 9)
+    neg = (ctypes.c_int32 * 2)(5, -1)
+    multi = lib.spdy_dp_solve_budgets
+    assert multi(fake, fake, 1, 1, 1, None, 2, fake, fake, fake, 1 << 20, None) == binding.ERR_NULL
+    assert multi(fake, fake, 1, 1, 1, one, 0, fake, fake, fake, 1 << 20, None) == binding.ERR_DIM
+    assert multi(fake, fake, 1, 1, 1, neg, 2, fake, fake, fake, 1 << 20, None) == binding.ERR_DIM
+    assert multi(fake, fake, 1, 1, 1, one, 2, fake, fake, fake, 8, None) == binding.ERR_WORKSPACE
     sens = lib.spdy_dp_solve_sensitivities
     assert sens(fake, None, fake, 1, 1, 1, 1, fake, fake, fake, 1 << 20, None) == binding.ERR_NULL
     assert sens(fake, fake, None, 1, 1, 1, 1, fake, fake, fake, 1 << 20, None) == binding.ERR_NULL

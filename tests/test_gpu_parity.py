@@ -245,6 +245,37 @@ def test_sensitivity_form_bit_exact(dp, compact):
         assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, "sensitivities")
 
 
+def test_several_budgets_from_one_fill(dp):
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(21)
+    cfg = workloads.CONFIGS["rn50_k1"]
+    tau, err, B = workloads.generate(cfg, K=24)
+    dense = int(tau[:, 0].sum())
+    fastest = int(tau.min(axis=1).sum())
+    cases = [(tau, err, [B, B // 2, fastest, fastest - 1, 0, (3 * B) // 4, B, dense, dense + 7])]
+    for (K, L, S, Bm) in [(3, 5, 6, 300), (4, 7, 70, 2500), (2, 6, 9, 30000)]:
+        t, e, _ = workloads.random_instance(rng, K, L, S, Bm, tau_max=max(1, Bm // L),
+                                            integer_err=3, zero_tau_frac=0.1, layer_floor=Bm // (3 * L))
+        cases.append((t, e, [Bm, Bm // 3, 0, Bm - 1, int(t.min(axis=1).sum()), Bm // 2]))
+    for tau, err, budgets in cases:
+        print(f"[parity] budgets {budgets} K={err.shape[0]} L={err.shape[1]} S={err.shape[2]}",
+              flush=True)
+        profile, cost = dp.spdy_dp_solve_budgets(torch.from_numpy(tau).to(dev),
+                                                 torch.from_numpy(err).to(dev), budgets)
+        torch.cuda.synchronize()
+        p_ref, c_ref = oracle.solve_budgets_ref(tau, err, budgets)
+        for j, b in enumerate(budgets):
+            assert_same(profile[j].cpu().numpy(), cost[j].cpu().numpy(), p_ref[j], c_ref[j],
+                        f"budget {b}")
+    # the level record does not keep the last row of D: a small workspace is refused
+    K, L, S = cases[0][1].shape
+    ws = dp.alloc_workspace(K, L, S, max(cases[0][2]), dev, compact=True)
+    with pytest.raises(dp.SpdyDpError) as e:
+        dp.spdy_dp_solve_budgets(torch.from_numpy(cases[0][0]).to(dev),
+                                 torch.from_numpy(cases[0][1]).to(dev), cases[0][2], workspace=ws)
+    assert e.value.status == -4
+
+
 def test_workspace_too_small_is_an_error(dp):
     dev = torch.device("cuda:0")
     tau = torch.ones((2, 2), dtype=torch.int32, device=dev)
