@@ -129,6 +129,28 @@ int spdy_dp_solve_budgets(const int32_t *tau, const float *err, int K, int L, in
                           const int32_t *budgets, int J, int16_t *profile, float *cost,
                           void *workspace, size_t workspace_bytes, void *stream);
 
+/* Re-solve K candidates that share their first layers with an already solved incumbent.  The
+ * coefficient search (Sec. 3.3, Alg. 4) proposes candidates by resampling a few sensitivities of
+ * the incumbent, so candidate k's errors equal the incumbent's for every layer before the first
+ * resampled one; D_l depends on layers 0..l only (Eq. 2), so those rows are the incumbent's and
+ * the fill starts at layer first_layer[k] from the incumbent's recorded row.  Results equal
+ * spdy_dp_solve_batched on the same err, bit for bit.
+ *   err          in  fp32 [K][L][S]  full tables; the CALLER guarantees err[k][l][:] equals the
+ *                                   incumbent's err[l][:] bit for bit for l < first_layer[k]
+ *   first_layer  in  int32 [K]       DEVICE; values are clamped to [0, L] (0 = solve from scratch,
+ *                                   L = identical to the incumbent)
+ *   incumbent_workspace              DEVICE; the workspace of a finished spdy_dp_solve_batched /
+ *                                   spdy_dp_fill call with K = 1, the same tau, L, S, B, and at
+ *                                   least spdy_dp_workspace_bytes(1, L, S, B) bytes (D record);
+ *                                   it is only read
+ * `workspace` (distinct from the incumbent's) needs spdy_dp_workspace_bytes(K, L, S, B) bytes; a
+ * smaller one of either returns SPDY_DP_ERR_WORKSPACE.  Candidates of one workgroup step through
+ * the layers together, so sorting the candidates by first_layer wastes the least. */
+int spdy_dp_solve_from_incumbent(const int32_t *tau, const float *err, const int32_t *first_layer,
+                                 int K, int L, int S, int B, const void *incumbent_workspace,
+                                 size_t incumbent_bytes, int16_t *profile, float *cost,
+                                 void *workspace, size_t workspace_bytes, void *stream);
+
 /* Test/debug accessor: where things are in a workspace of `workspace_bytes` bytes.
  *   out[0] variant: 0 = fp32 D record, 1 = one-byte level record
  *   out[1] byte offset of the int32 header: [0] B - M (or -1 if M > B: nobody is feasible),

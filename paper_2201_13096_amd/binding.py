@@ -18,8 +18,8 @@ OK = 0
 ERR_NULL, ERR_DIM, ERR_LEVELS, ERR_WORKSPACE, ERR_OVERFLOW, ERR_LAUNCH = -1, -2, -3, -4, -5, -9
 
 EXPORTS = ("spdy_dp_workspace_bytes", "spdy_dp_workspace_bytes_min", "spdy_dp_solve_batched",
-           "spdy_dp_solve_sensitivities", "spdy_dp_solve_budgets", "spdy_dp_fill",
-           "spdy_dp_backtrace",
+           "spdy_dp_solve_sensitivities", "spdy_dp_solve_budgets",
+           "spdy_dp_solve_from_incumbent", "spdy_dp_fill", "spdy_dp_backtrace",
            "spdy_dp_workspace_layout", "spdy_dp_strerror")
 
 
@@ -50,6 +50,9 @@ def lib() -> ctypes.CDLL:
         L.spdy_dp_solve_budgets.restype = i
         L.spdy_dp_solve_budgets.argtypes = [vp, vp, i, i, i, ctypes.POINTER(ctypes.c_int32), i, vp,
                                             vp, vp, sz, vp]
+        L.spdy_dp_solve_from_incumbent.restype = i
+        L.spdy_dp_solve_from_incumbent.argtypes = [vp, vp, vp, i, i, i, i, vp, sz, vp, vp, vp, sz,
+                                                   vp]
         L.spdy_dp_fill.restype = i
         L.spdy_dp_fill.argtypes = [vp, vp, i, i, i, i, vp, vp, sz, vp]
         L.spdy_dp_backtrace.restype = i
@@ -191,6 +194,34 @@ def spdy_dp_solve_budgets(tau, err, budgets, profile=None, cost=None, workspace=
     st = lib().spdy_dp_solve_budgets(tau.data_ptr(), err.data_ptr(), K, L, S, arr, J,
                                      profile.data_ptr(), cost.data_ptr(), workspace.data_ptr(),
                                      workspace.numel(), _stream(stream))
+    if st != OK:
+        raise SpdyDpError(st)
+    return profile, cost
+
+
+def spdy_dp_solve_from_incumbent(tau, err, first_layer, B: int, incumbent_workspace,
+                                 profile=None, cost=None, workspace=None, stream=None):
+    """Re-solve candidates whose tables equal a solved incumbent's before ``first_layer[k]``."""
+    tau = _dev(tau, torch.int32, "tau")
+    err = _dev(err, torch.float32, "err")
+    first_layer = _dev(first_layer, torch.int32, "first_layer")
+    _dev(incumbent_workspace, torch.uint8, "incumbent_workspace")
+    K, L, S = _shapes(tau, err)
+    if first_layer.numel() != K:
+        raise ValueError("first_layer must have K entries")
+    if profile is None:
+        profile = torch.empty((K, L), dtype=torch.int16, device=err.device)
+    if cost is None:
+        cost = torch.empty((K,), dtype=torch.float32, device=err.device)
+    if workspace is None:
+        workspace = alloc_workspace(K, L, S, B, err.device)
+    _dev(profile, torch.int16, "profile")
+    _dev(cost, torch.float32, "cost")
+    _dev(workspace, torch.uint8, "workspace")
+    st = lib().spdy_dp_solve_from_incumbent(
+        tau.data_ptr(), err.data_ptr(), first_layer.data_ptr(), K, L, S, int(B),
+        incumbent_workspace.data_ptr(), incumbent_workspace.numel(), profile.data_ptr(),
+        cost.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream))
     if st != OK:
         raise SpdyDpError(st)
     return profile, cost

@@ -340,6 +340,22 @@ struct ErrSource {
     }
 };
 
+// Re-solving candidates that share their first layers with an already solved incumbent
+// (Alg. 4 resamples a few sensitivities of the incumbent): candidate k's tables equal the
+// incumbent's for layers < first_layer[k], so its rows of D do too, and the fill starts at
+// layer first_layer[k] from the incumbent's recorded row first_layer[k] - 1.
+struct Resume {
+    const int32_t *first_layer;   // [K] in [0, L], or nullptr: every candidate starts at layer 0
+    const float *inc_rec;         // the incumbent's D record, float [L][pitch]
+    __device__ __forceinline__ int start(int k, int L) const
+    {
+        if (!first_layer)
+            return 0;
+        const int f = first_layer[k];
+        return f < 0 ? 0 : (f > L ? L : f);
+    }
+};
+
 struct LevelEntry {   // one visited level of one layer of one candidate
     int32_t shift;    // tau - m_l (INT32_MAX in padding entries)
     float err;
@@ -536,7 +552,7 @@ __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
     ErrSource src, const int32_t *__restrict__ meta, const int32_t *__restrict__ shifts,
     const int32_t *__restrict__ order, int path, int K, int L,
     int S, int s8, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
-    float *__restrict__ rows, int32_t *__restrict__ tstar, float *__restrict__ cost)
+    float *__restrict__ rows, int32_t *__restrict__ tstar, float *__restrict__ cost, Resume resume)
 {
     extern __shared__ float lds[];
     __shared__ float s_best[kFillWaves];
@@ -587,6 +603,21 @@ __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
     const int32_t *nact = meta + kMetaHeader + L;
     const size_t ke = active ? k : 0;            // candidate whose errors this wave reads
 
+    // a candidate that shares its first l0 layers with the incumbent starts from the incumbent's
+    // row l0 - 1, placed where layer l0 reads its previous row
+    const int l0 = active ? resume.start(k, L) : 0;
+    if (l0 > 0) {
+        float *dst = (l0 & 1) ? buf1 : buf0;
+        const float *from = resume.inc_rec + (size_t)(l0 - 1) * pitch;
+        const int n = nact[l0 - 1] * kWave;
+        for (int t = wv * kWave + lane; t < n; t += tw * kWave)
+            dst[t] = from[t];
+        if (wv == 0 && lane == 0 && dst != buf0)
+            buf0[0] = __builtin_inff();          // undo the layer-0 start value
+    }
+    if (resume.first_layer)
+        __syncthreads();
+
     // lane i keeps visited level i of the layer being swept; the next layer's is fetched early
     LevelEntry next_first = load_level(shifts, order, src.row(ke, 0, L, S), s8, 0, lane);
     for (int l = 0; l < L; ++l) {
@@ -597,7 +628,7 @@ __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
         const float *prev = (l & 1) ? buf1 : buf0;
         float *cur = (l & 1) ? buf0 : buf1;
         int c = 0, c_end = 0;
-        if (active) {
+        if (active && l >= l0) {
             const int n = nact[l];               // chunks of this row that can be finite
             c = (int)((long long)wv * n / tw);
             c_end = (int)((long long)(wv + 1) * n / tw);
@@ -784,7 +815,7 @@ __global__ __launch_bounds__(kWalkThreads) void dp_backtrace_values(
     const int32_t *__restrict__ tau, ErrSource src, const int32_t *__restrict__ meta,
     const float *__restrict__ drec,
     const int32_t *__restrict__ tstar, int K, int L, int S, int pitch,
-    int16_t *__restrict__ profile, float *__restrict__ cost)
+    int16_t *__restrict__ profile, float *__restrict__ cost, Resume resume)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int k = blockIdx.x * (kWalkThreads / kWave) + threadIdx.x / kWave;
@@ -798,13 +829,17 @@ __global__ __launch_bounds__(kWalkThreads) void dp_backtrace_values(
         return;
     }
     const float *drec_k = drec + (size_t)k * L * pitch;
-    float target = drec_k[(size_t)(L - 1) * pitch + t];
+    const int l0 = resume.start(k, L);           // rows below l0 are the incumbent's
+    auto row_of = [&](int l) {
+        return (l < l0 ? resume.inc_rec : drec_k) + (size_t)l * pitch;
+    };
+    float target = row_of(L - 1)[t];
     LayerLevels<kLevelBlocks> next =
         load_layer<kLevelBlocks>(tau, src.row(k, L - 1, L, S), meta, L - 1, L, S, lane);
     bool ok = true;
     for (int l = L - 1; l >= 0; --l) {
         const LayerLevels<kLevelBlocks> cur = next;
-        const float *prow = drec_k + (size_t)(l > 0 ? l - 1 : 0) * pitch;   // row of layer l - 1
+        const float *prow = row_of(l > 0 ? l - 1 : 0);       // row of layer l - 1
         // issue the gather of D_{l-1} first, then the next layer's table behind it
         int u[kLevelBlocks];
         float pv[kLevelBlocks];
@@ -867,8 +902,8 @@ int launch_status()
 }
 
 template <bool kLevel>
-int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, int K, int L, int S,
-                int B, char *ws, float *cost, hipStream_t q)
+int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume resume, int K, int L,
+                int S, int B, char *ws, float *cost, hipStream_t q)
 {
     int32_t *meta = reinterpret_cast<int32_t *>(ws + lay.meta_off);
     int32_t *shifts = reinterpret_cast<int32_t *>(ws + lay.shifts_off);
@@ -908,13 +943,13 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, int K, int
                        kLevel ? kMaxGroupLevel : kMaxGroup, lds_small, lds_large, kLevel ? 0 : 1,
                        meta, shifts, order);
     hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, shifts, order,
-                       1, K, L, S, s8, pitch, choice, drec, rows, tstar, cost);
+                       1, K, L, S, s8, pitch, choice, drec, rows, tstar, cost, resume);
     if (lds_large)
         hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, shifts,
-                           order, 2, K, L, S, s8, pitch, choice, drec, rows, tstar, cost);
+                           order, 2, K, L, S, s8, pitch, choice, drec, rows, tstar, cost, resume);
     if (lay.may_spill)
         hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, src, meta, shifts, order,
-                           0, K, L, S, s8, pitch, choice, drec, rows, tstar, cost);
+                           0, K, L, S, s8, pitch, choice, drec, rows, tstar, cost, resume);
     return launch_status();
 }
 
@@ -928,7 +963,7 @@ int validate(const Layout &lay, const void *workspace)
 }
 
 int fill_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B, float *cost,
-              void *workspace, size_t workspace_bytes, void *stream)
+              void *workspace, size_t workspace_bytes, void *stream, Resume resume = Resume{})
 {
     if (!tau || !cost)
         return SPDY_DP_ERR_NULL;
@@ -940,13 +975,13 @@ int fill_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B, flo
     char *ws = static_cast<char *>(workspace);
     (void)hipGetLastError();
     return lay.variant == kLevelRecord
-               ? launch_fill<true>(lay, tau, src, K, L, S, B, ws, cost, q)
-               : launch_fill<false>(lay, tau, src, K, L, S, B, ws, cost, q);
+               ? launch_fill<true>(lay, tau, src, resume, K, L, S, B, ws, cost, q)
+               : launch_fill<false>(lay, tau, src, resume, K, L, S, B, ws, cost, q);
 }
 
 int backtrace_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B,
                    int16_t *profile, float *cost, const void *workspace, size_t workspace_bytes,
-                   void *stream)
+                   void *stream, Resume resume = Resume{})
 {
     if (!tau || !profile || !cost)
         return SPDY_DP_ERR_NULL;
@@ -968,7 +1003,7 @@ int backtrace_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B
         hipLaunchKernelGGL(S <= kWave ? dp_backtrace_values<1> : dp_backtrace_values<4>,
                            dim3((K + per_block - 1) / per_block), dim3(kWalkThreads), 0, q, tau,
                            src, meta, reinterpret_cast<const float *>(ws + lay.record_off), tstar,
-                           K, L, S, (int)lay.row, profile, cost);
+                           K, L, S, (int)lay.row, profile, cost, resume);
     }
     return launch_status();
 }
@@ -1023,6 +1058,36 @@ int budgets_impl(const int32_t *tau, ErrSource src, int K, int L, int S, const i
             return st;
     }
     return SPDY_DP_OK;
+}
+
+int resume_impl(const int32_t *tau, ErrSource src, const int32_t *first_layer, int K, int L, int S,
+                int B, const void *incumbent, size_t incumbent_bytes, int16_t *profile,
+                float *cost, void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!tau || !first_layer || !incumbent || !profile || !cost)
+        return SPDY_DP_ERR_NULL;
+    const Layout lay = make_layout(K, L, S, B, workspace_bytes);
+    int st = validate(lay, workspace);
+    if (st != SPDY_DP_OK)
+        return st;
+    const Layout inc = make_layout(1, L, S, B, incumbent_bytes);
+    if (inc.status != SPDY_DP_OK)
+        return inc.status;
+    if (lay.variant != kValueRecord || inc.variant != kValueRecord)
+        return SPDY_DP_ERR_WORKSPACE;            // rows of D are only kept in the D record
+    const char *a = static_cast<const char *>(incumbent);
+    const char *b = static_cast<const char *>(workspace);
+    if (a < b + workspace_bytes && b < a + incumbent_bytes)
+        return SPDY_DP_ERR_WORKSPACE;            // the fill would overwrite the rows it resumes from
+    Resume resume;
+    resume.first_layer = first_layer;
+    resume.inc_rec =
+        reinterpret_cast<const float *>(static_cast<const char *>(incumbent) + inc.record_off);
+    st = fill_impl(tau, src, K, L, S, B, cost, workspace, workspace_bytes, stream, resume);
+    if (st != SPDY_DP_OK)
+        return st;
+    return backtrace_impl(tau, src, K, L, S, B, profile, cost, workspace, workspace_bytes, stream,
+                          resume);
 }
 
 }  // namespace
@@ -1104,6 +1169,18 @@ int spdy_dp_solve_budgets(const int32_t *tau, const float *err, int K, int L, in
         return SPDY_DP_ERR_NULL;
     return budgets_impl(tau, ErrSource{err, nullptr, nullptr}, K, L, S, budgets, J, profile, cost,
                         workspace, workspace_bytes, stream);
+}
+
+int spdy_dp_solve_from_incumbent(const int32_t *tau, const float *err, const int32_t *first_layer,
+                                 int K, int L, int S, int B, const void *incumbent_workspace,
+                                 size_t incumbent_bytes, int16_t *profile, float *cost,
+                                 void *workspace, size_t workspace_bytes, void *stream)
+{
+    if (!err)
+        return SPDY_DP_ERR_NULL;
+    return resume_impl(tau, ErrSource{err, nullptr, nullptr}, first_layer, K, L, S, B,
+                       incumbent_workspace, incumbent_bytes, profile, cost, workspace,
+                       workspace_bytes, stream);
 }
 
 const char *spdy_dp_strerror(int status)

@@ -112,6 +112,29 @@ def test_argument_errors_are_reported_before_any_launch(binding):
     assert sens(fake, fake, None, 1, 1, 1, 1, fake, fake, fake, 1 << 20, None) == binding.ERR_NULL
     assert sens(fake, fake, fake, 1, 1, 300, 1, fake, fake, fake, 1 << 20, None) == \
         binding.ERR_LEVELS
+    inc = lib.spdy_dp_solve_from_incumbent
+    big = 1 << 20
+    far = 0x40000000
+    assert inc(fake, fake, None, 1, 1, 1, 1, far, big, fake, fake, fake, big, None) == \
+        binding.ERR_NULL
+    assert inc(fake, None, fake, 1, 1, 1, 1, far, big, fake, fake, fake, big, None) == \
+        binding.ERR_NULL
+    assert inc(fake, fake, fake, 1, 1, 1, 1, None, big, fake, fake, fake, big, None) == \
+        binding.ERR_NULL
+    assert inc(fake, fake, fake, 1, 0, 1, 1, far, big, fake, fake, fake, big, None) == \
+        binding.ERR_DIM
+    assert inc(fake, fake, fake, 1, 1, 1, 1, far, 8, fake, fake, fake, big, None) == \
+        binding.ERR_WORKSPACE
+    assert inc(fake, fake, fake, 1, 1, 1, 1, far, big, fake, fake, fake, 8, None) == \
+        binding.ERR_WORKSPACE
+    # overlapping workspaces: the fill would overwrite the rows it resumes from
+    assert inc(fake, fake, fake, 1, 1, 1, 1, fake + 64, big, fake, fake, fake, big, None) == \
+        binding.ERR_WORKSPACE
+    # a level-record workspace keeps no rows of D to resume from
+    small = binding.lib().spdy_dp_workspace_bytes_min(4, 8, 8, 1000)
+    assert small < binding.lib().spdy_dp_workspace_bytes(4, 8, 8, 1000)
+    assert inc(fake, fake, fake, 4, 8, 8, 1000, far, big, fake, fake, fake, small, None) == \
+        binding.ERR_WORKSPACE
     assert lib.spdy_dp_fill(fake, fake, 1, 1, 1, 1, None, fake, 1 << 20, None) == binding.ERR_NULL
     bt = lib.spdy_dp_backtrace
     assert bt(fake, fake, 1, 1, 1, 1, None, fake, fake, 1 << 20, None) == binding.ERR_NULL

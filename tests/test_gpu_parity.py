@@ -276,6 +276,98 @@ def test_several_budgets_from_one_fill(dp):
     assert e.value.status == -4
 
 
+def mutate_from(rng, base, first_layer, err_draw):
+    """Candidates that equal `base` [L, S] before first_layer[k] and differ (at that layer and at
+    a random subset of the later ones) from it after."""
+    K = first_layer.size
+    L, S = base.shape
+    err = np.repeat(base[None], K, axis=0)
+    for k in range(K):
+        f = int(np.clip(first_layer[k], 0, L))
+        for l in range(f, L):
+            if l == f or rng.random() < 0.3:
+                err[k, l] = err_draw(l)
+    return np.ascontiguousarray(err)
+
+
+RESUME_SHAPES = [
+    # (L, S, B, K, tau_max): rows in registers with teams, one team per workgroup, the large LDS
+    # rows, the rows in global memory, and more than 64 levels
+    (6, 5, 300, 37, None),
+    (9, 8, 2000, 21, 400),
+    (54, 40, 10000, 48, None),
+    (12, 40, 30000, 9, 4000),
+    (5, 12, 70000, 5, 20000),
+    (7, 130, 5000, 11, 900),
+]
+
+
+@pytest.mark.parametrize("shape", RESUME_SHAPES, ids=lambda s: "L%d_S%d_B%d_K%d" % s[:4])
+def test_resume_from_incumbent_bit_exact(dp, shape):
+    L, S, B, K, tau_max = shape
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(L * 1000 + S)
+    if (L, S, B) == (54, 40, 10000):
+        tau, base, _ = workloads.generate(workloads.CONFIGS["rn50_k1"], seed=5)
+        w = np.square(workloads.level_grid(S, 0.9))
+        draw = lambda l: (rng.random() * w).astype(np.float32)
+    else:
+        tau, base, _ = workloads.random_instance(rng, 1, L, S, B, tau_max=tau_max, integer_err=4,
+                                                 zero_tau_frac=0.05, layer_floor=B // (4 * L))
+        draw = lambda l: rng.integers(0, 4, size=S).astype(np.float32)
+    first_layer = rng.integers(0, L + 1, size=K).astype(np.int32)
+    first_layer[:4] = [0, L, 1, L - 1]
+    first_layer[4] = -3          # clamped to 0
+    err = mutate_from(rng, base[0], first_layer, draw)
+    given = first_layer.copy()
+    if K > 8:
+        given[5] = L + 9         # clamped to L: candidate 5 must then equal the incumbent
+        err[5] = base[0]
+    print(f"[parity] resume L={L} S={S} B={B} K={K}", flush=True)
+    tau_d = torch.from_numpy(tau).to(dev)
+    inc_ws = dp.alloc_workspace(1, L, S, B, dev)
+    inc_ws.fill_(0xAB)
+    p_inc, c_inc = dp.spdy_dp_solve_batched(tau_d, torch.from_numpy(base).to(dev), B,
+                                            workspace=inc_ws)
+    ws = dp.alloc_workspace(K, L, S, B, dev)
+    ws.fill_(0xCD)
+    for order in ("given", "sorted"):
+        idx = np.arange(K) if order == "given" else np.argsort(given, kind="stable")
+        profile, cost = dp.spdy_dp_solve_from_incumbent(
+            tau_d, torch.from_numpy(err[idx]).to(dev), torch.from_numpy(given[idx]).to(dev), B,
+            inc_ws, workspace=ws)
+        torch.cuda.synchronize()
+        p_ref, c_ref = oracle.solve_ref(tau, err[idx], B, threads=CPU_THREADS)
+        assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, f"resume {order}")
+    # the incumbent's workspace was only read: solving from it again still works
+    p_ref, c_ref = oracle.solve_ref(tau, base, B)
+    assert_same(p_inc.cpu().numpy(), c_inc.cpu().numpy(), p_ref, c_ref, "incumbent")
+    profile, cost = dp.spdy_dp_solve_from_incumbent(
+        tau_d, torch.from_numpy(base).to(dev), torch.full((1,), L, dtype=torch.int32, device=dev),
+        B, inc_ws)
+    torch.cuda.synchronize()
+    assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, "incumbent again")
+
+
+def test_resume_from_an_infeasible_incumbent(dp):
+    dev = torch.device("cuda:0")
+    tau = np.array([[5, 6], [7, 9], [4, 4]], dtype=np.int32)
+    base = np.array([[[1, 0], [2, 1], [0, 3]]], dtype=np.float32)
+    for B in (15, 16, 17):       # the fastest profile takes 16
+        tau_d = torch.from_numpy(tau).to(dev)
+        inc_ws = dp.alloc_workspace(1, 3, 2, B, dev)
+        dp.spdy_dp_solve_batched(tau_d, torch.from_numpy(base).to(dev), B, workspace=inc_ws)
+        err = np.repeat(base, 4, axis=0)
+        err[1, 2] = [5, 0]
+        err[2, 1] = [0, 9]
+        first = np.array([3, 2, 1, 0], dtype=np.int32)
+        profile, cost = dp.spdy_dp_solve_from_incumbent(
+            tau_d, torch.from_numpy(err).to(dev), torch.from_numpy(first).to(dev), B, inc_ws)
+        torch.cuda.synchronize()
+        p_ref, c_ref = oracle.solve_ref(tau, err, B)
+        assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, f"B={B}")
+
+
 def test_workspace_too_small_is_an_error(dp):
     dev = torch.device("cuda:0")
     tau = torch.ones((2, 2), dtype=torch.int32, device=dev)
