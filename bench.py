@@ -36,10 +36,12 @@ LDS_BYTES_PER_UPDATE = 4
 MEASURED_TRAFFIC_BYTES = {("rn50_k1024", "d"): 957e6, ("rn50_k1024", "level"): 246e6}
 
 
-def executed_updates_per_candidate(tau: np.ndarray, B: int) -> int:
+def executed_updates_per_candidate(tau: np.ndarray, B: int, merge_equal_times: bool) -> int:
     """Inner-loop trips of Alg. 1 on the table the device actually fills: times reduced by each
     layer's minimum (budget B - M) and rows cut at the largest reachable reduced time.  Level s
-    of layer l then visits t' = shift .. top_l."""
+    of layer l then visits t' = shift .. top_l.  With the D record, levels of a layer that take
+    the same time are served by one update (the smallest of their errors), so only the distinct
+    times of a layer count."""
     t = tau.astype(np.int64)
     mn = t.min(axis=1)
     bp = B - int(mn.sum())
@@ -48,7 +50,10 @@ def executed_updates_per_candidate(tau: np.ndarray, B: int) -> int:
     delta = t - mn[:, None]
     span = np.where(delta <= bp, delta, 0).max(axis=1)
     top = np.minimum(np.cumsum(span), bp)
-    return int(np.clip(top[:, None] + 1 - delta, 0, None).sum())
+    if not merge_equal_times:
+        return int(np.clip(top[:, None] + 1 - delta, 0, None).sum())
+    return int(sum(np.clip(top[l] + 1 - np.unique(delta[l]), 0, None).sum()
+                   for l in range(t.shape[0])))
 
 
 def main() -> int:
@@ -156,7 +161,7 @@ def main() -> int:
     fill_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
 
     nominal = K * L * S * B
-    executed = K * executed_updates_per_candidate(tau, B)
+    executed = K * executed_updates_per_candidate(tau, B, args.record == "d")
     value = nominal / (ms_per_step * 1e-3)
     ops = LANE_OPS_PER_UPDATE[args.record]
     achieved = executed * ops / (fill_ms * 1e-3)

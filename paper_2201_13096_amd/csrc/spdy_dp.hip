@@ -41,7 +41,7 @@ constexpr int kMaxGroupLevel = 10;   // same when the level is tracked too (more
 constexpr int kFillThreads = 1024;
 constexpr int kFillWaves = kFillThreads / kWave;
 constexpr int kWalkThreads = 256;    // D-record walk back: 4 waves = 4 candidates per workgroup
-constexpr int kLdsStatic = 256;           // room for the fill kernel's static LDS (argmin scratch)
+constexpr int kLdsStatic = 8192 + 256;    // the fill kernel's static LDS (entry tables, argmin)
 constexpr int kLdsBytes = 160 * 1024 - kLdsStatic;       // dynamic LDS a workgroup can get
 constexpr int kLdsHalf = 80 * 1024 - kLdsStatic;         // lets two workgroups share a compute unit
 constexpr int kHalo = kMaxGroup * kWave;  // +inf apron left of every row (one group width)
@@ -70,8 +70,10 @@ struct Layout {
     bool may_spill;      // rows of the full budget may exceed LDS: the global-row launch is needed
     size_t s8;           // levels per layer padded to a multiple of kBatch
     size_t meta_off;     // int32 meta[kMetaHeader + 2 L]
-    size_t shifts_off;   // int32 shifts[L][s8]: tau - m_l of the r-th visited level
-    size_t order_off;    // int32 order[L][s8]: index of the r-th visited level
+    size_t shifts_off;   // int32 shifts[L][s8]: tau - m_l of the r-th visited entry
+    size_t order_off;    // int32 order[L][s8]: level index at position r of the visiting order
+    size_t start_off;    // int32 start[L][s8 + kBatch]: first position of entry r (D record)
+    size_t entry_off;    // int32 entry[L][s8]: the entry that level s belongs to (D record)
     size_t tstar_off;    // int32 tstar[K]
     size_t record_off;   // float D[K][L][row]  or  uint8 P[K][L][row]
     size_t rows_value;   // float rows[K][2][kHalo + row] after the record, when may_spill
@@ -112,7 +114,10 @@ Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes)
     lay.meta_off = 0;
     lay.shifts_off = align_up((kMetaHeader + 2 * (size_t)L) * sizeof(int32_t), kAlign);
     lay.order_off = align_up(lay.shifts_off + (size_t)L * lay.s8 * sizeof(int32_t), kAlign);
-    lay.tstar_off = align_up(lay.order_off + (size_t)L * lay.s8 * sizeof(int32_t), kAlign);
+    lay.start_off = align_up(lay.order_off + (size_t)L * lay.s8 * sizeof(int32_t), kAlign);
+    lay.entry_off =
+        align_up(lay.start_off + (size_t)L * (lay.s8 + kBatch) * sizeof(int32_t), kAlign);
+    lay.tstar_off = align_up(lay.entry_off + (size_t)L * lay.s8 * sizeof(int32_t), kAlign);
     lay.record_off = align_up(lay.tstar_off + (size_t)K * sizeof(int32_t), kAlign);
     const size_t rows = lay.may_spill ? 2 * (size_t)K * row_bytes : 0;
     lay.rows_value = align_up(lay.record_off + (size_t)K * L * lay.row * sizeof(float), kAlign);
@@ -259,15 +264,24 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int L, int S, in
     }
 }
 
-// Prepare, workgroup 1 + l: the order in which the fill visits the levels of layer l, and their
-// shifts tau - m_l in that order; padding up to s8 gets shift INT32_MAX, which no group of
-// buckets can use.  When only the minimum is needed (D record) the levels are visited by
-// ascending shift, ties by index, so the levels a group of buckets can use form a prefix; when
-// the level itself is tracked the order stays ascending in s (ties then go to the smallest s
-// through the strict "<").  One thread per level (S <= 255).
+// Prepare, workgroup 1 + l: what the fill visits in layer l, in which order, with the shifts
+// tau - m_l; padding up to s8 gets shift INT32_MAX, which no group of buckets can use.
+//   level tracked (sorted = 0): one entry per level, ascending in s, so that ties go to the
+//     smallest s through the strict "<"; entry r is level r.
+//   D record (sorted = 1): the levels are ordered by ascending shift, ties by index, and levels
+//     with the SAME shift form one entry: they read the same cell of D_{l-1}, and a rounded add
+//     is monotone in the addend, so min_s fl(p + e_s) = fl(p + min_s e_s) bit for bit (up to
+//     the sign of a zero): one update with the smallest error of the entry's levels serves them
+//     all.  Entry r covers positions start[r] .. start[r + 1] - 1 of `order`, level s belongs
+//     to entry entry[s]; the entries a group of buckets can use form a prefix.
+// One thread per level (S <= 255).
 __device__ void prepare_order(const int32_t *__restrict__ tau, int l, int S, int s8, int sorted,
-                              int32_t *__restrict__ shifts, int32_t *__restrict__ order)
+                              int32_t *__restrict__ shifts, int32_t *__restrict__ order,
+                              int32_t *__restrict__ start, int32_t *__restrict__ entry_of)
 {
+    __shared__ int32_t s_shift[256];
+    __shared__ int32_t s_level[256];
+    __shared__ int s_entries;
     const int s = threadIdx.x;
     int32_t *shifts_l = shifts + (size_t)l * s8;
     int32_t *order_l = order + (size_t)l * s8;
@@ -282,11 +296,40 @@ __device__ void prepare_order(const int32_t *__restrict__ tau, int l, int S, int
         }
         if (!sorted)
             rank = s;
-        shifts_l[rank] = mine - m;
         order_l[rank] = s;
+        if (sorted) {
+            s_shift[rank] = mine - m;
+            s_level[rank] = s;
+        } else {
+            shifts_l[rank] = mine - m;
+        }
     } else if (s < s8) {
-        shifts_l[s] = INT32_MAX;
         order_l[s] = 0;
+        if (!sorted)
+            shifts_l[s] = INT32_MAX;
+    }
+    if (!sorted)
+        return;
+    __syncthreads();
+    int32_t *start_l = start + (size_t)l * (s8 + kBatch);
+    const int r = threadIdx.x;                    // a position of the sorted order
+    if (r < S) {
+        int entry = 0;                            // distinct shifts before position r
+        for (int o = 1; o <= r; ++o)
+            entry += s_shift[o] != s_shift[o - 1] ? 1 : 0;
+        if (r == 0 || s_shift[r] != s_shift[r - 1]) {
+            shifts_l[entry] = s_shift[r];
+            start_l[entry] = r;
+        }
+        entry_of[(size_t)l * s8 + s_level[r]] = entry;
+        if (r == S - 1)
+            s_entries = entry + 1;
+    }
+    __syncthreads();
+    for (int e = s_entries + r; e < s8 + kBatch; e += 256) {
+        start_l[e] = S;                           // the last entry ends here; padding is empty
+        if (e < s8)
+            shifts_l[e] = INT32_MAX;
     }
 }
 
@@ -295,12 +338,14 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
                                                   int lds_small, int lds_large, int sorted,
                                                   int32_t *__restrict__ meta,
                                                   int32_t *__restrict__ shifts,
-                                                  int32_t *__restrict__ order)
+                                                  int32_t *__restrict__ order,
+                                                  int32_t *__restrict__ start,
+                                                  int32_t *__restrict__ entry_of)
 {
     if (blockIdx.x == 0)
         prepare_budget(tau, L, S, B, waves, max_group, lds_small, lds_large, meta);
     else
-        prepare_order(tau, blockIdx.x - 1, S, s8, sorted, shifts, order);
+        prepare_order(tau, blockIdx.x - 1, S, s8, sorted, shifts, order, start, entry_of);
 }
 
 // ---------------------------------------------------------------------------------------------
@@ -361,20 +406,99 @@ struct LevelEntry {   // one visited level of one layer of one candidate
     float err;
 };
 
-// This lane's entry of the 64 visited levels of a layer starting at position `blk`.
-__device__ __forceinline__ LevelEntry load_level(const int32_t *__restrict__ shifts_l,
-                                                 const int32_t *__restrict__ order_l,
-                                                 ErrRow er, int s8, int blk, int lane)
+// The prepare kernel's tables of one layer (see prepare_order).
+struct LayerTable {
+    const int32_t *shift;   // [s8]
+    const int32_t *order;   // [s8]
+    const int32_t *start;   // [s8 + kBatch], D record only
+    const int32_t *entry;   // [s8], D record only
+};
+struct LevelTables {
+    const int32_t *shifts, *order, *start, *entry;
+    int s8;
+    __device__ __forceinline__ LayerTable layer(int l) const
+    {
+        return LayerTable{shifts + (size_t)l * s8, order + (size_t)l * s8,
+                          start + (size_t)l * (s8 + kBatch), entry + (size_t)l * s8};
+    }
+};
+
+// This lane's entry of the 64 visited entries of a layer starting at entry `blk`.  With the D
+// record an entry stands for all levels of one shift and carries the smallest of their errors.
+template <bool kLevel>
+__device__ __forceinline__ LevelEntry load_level(LayerTable tl, ErrRow er, int s8, int blk,
+                                                 int lane)
 {
     LevelEntry p;
     p.shift = INT32_MAX;
     p.err = __builtin_inff();
-    if (blk + lane < s8) {
-        p.shift = shifts_l[blk + lane];
-        p.err = er.at(order_l[blk + lane]);
+    const int r = blk + lane;
+    if (r < s8) {
+        p.shift = tl.shift[r];
+        if constexpr (kLevel) {
+            p.err = er.at(tl.order[r]);
+        } else {
+            const int end = tl.start[r + 1];
+            for (int j = tl.start[r]; j < end; ++j) {
+                const float e = er.at(tl.order[j]);
+                p.err = e < p.err ? e : p.err;
+            }
+        }
     }
     return p;
 }
+
+// Layers of at most 64 levels (one lane per level): what a wave loads for the NEXT layer while
+// it sweeps a layer.  No load depends on another, so all are in flight during the sweep.
+//   shift : shift of entry `lane` (every wave)
+//   raw   : error of level `lane`; with the level record entry r is level r and this is the
+//           entry's error; with the D record only the first wave of a team loads it, with
+//   entry : the entry level `lane` belongs to, and folds the errors of a team's candidate into
+//           the team's table in LDS with one atomic min per lane (publish_entries).
+struct LevelFetch {
+    int32_t shift;
+    float raw;
+    int32_t entry;
+};
+
+template <bool kLevel>
+__device__ __forceinline__ LevelFetch fetch_levels(LayerTable tl, ErrRow er, int S, int s8,
+                                                   int lane, bool producer)
+{
+    LevelFetch f;
+    f.shift = lane < s8 ? tl.shift[lane] : INT32_MAX;
+    f.raw = __builtin_inff();
+    f.entry = 0;
+    if (lane < S && (kLevel || producer)) {
+        f.raw = er.at(lane);
+        if constexpr (!kLevel)
+            f.entry = tl.entry[lane];
+    }
+    return f;
+}
+
+// table[r] = smallest error among the levels of entry r (+inf for unused entries); one wave.
+__device__ __forceinline__ void publish_entries(float *table, const LevelFetch &f, int S, int lane)
+{
+    table[lane] = __builtin_inff();
+    if (lane < S)
+        __hip_atomic_fetch_min(&table[f.entry], f.raw, __ATOMIC_RELAXED,
+                               __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+
+// The table words of the next layer that are still being loaded while a layer is swept.  Loads
+// and stores retire through one in-order counter, so a wait for these loads placed after the
+// record stores of a layer would also wait for those stores; `settle` makes the compiler wait
+// for the loads where it is called (right after the sweep, when they have long arrived).
+struct Pending {
+    const LevelFetch *fetch;
+    const LevelEntry *entry;
+    __device__ __forceinline__ void settle() const
+    {
+        asm volatile("" ::"v"(fetch->raw), "v"(fetch->shift), "v"(fetch->entry),
+                     "v"(entry->shift), "v"(entry->err));
+    }
+};
 
 __device__ __forceinline__ float lane_value(float v, int lane)
 {
@@ -384,16 +508,14 @@ __device__ __forceinline__ float lane_value(float v, int lane)
 // The levels of one layer swept over one group of R chunks (R*64 consecutive reduced buckets
 // from t0); best[j] / arg[j] belong to bucket t0 + 64*j + lane.
 //   prev  : row of the previous layer, prev[-kHalo .. -1] reads +inf
-//   first : lane i holds visited level i of the layer (positions 0..63)
-//   shifts_l / order_l / er : the layer's tables, for positions >= 64
+//   first : lane i holds visited entry i of the layer (entries 0..63)
+//   tl / er : the layer's tables, for entries >= 64
 // A level applies to the group if its shift does not exceed the group's last bucket; lanes
 // left of the shift then read the +inf apron.  The applicable levels of a 64-block are found
 // with one ballot and walked in ascending position.
 template <int R, bool kLevel>
 __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, LevelEntry first,
-                                            const int32_t *__restrict__ shifts_l,
-                                            const int32_t *__restrict__ order_l,
-                                            ErrRow er, int s8, int t0, int lane,
+                                            LayerTable tl, ErrRow er, int s8, int t0, int lane,
                                             float (&best)[R], unsigned (&arg)[R])
 {
 #pragma unroll
@@ -409,7 +531,7 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, Leve
 
     for (int blk = 0; blk < s8; blk += kWave) {
         const LevelEntry mine =
-            blk == 0 ? first : load_level(shifts_l, order_l, er, s8, blk, lane);
+            blk == 0 ? first : load_level<kLevel>(tl, er, s8, blk, lane);
         unsigned long long use = __ballot(mine.shift <= last);
         if constexpr (kLevel) {
             while (use) {
@@ -459,17 +581,18 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, Leve
 // with R = 0 if it has no chunks).
 template <int R, bool kLevel, bool inplace>
 __device__ __forceinline__ void fill_group(const float *prev, float *cur, uint8_t *choice,
-                                           float *rec, LevelEntry first, const int32_t *shifts_l,
-                                           const int32_t *order_l, ErrRow er, int s8, int t0,
-                                           int lane)
+                                           float *rec, LevelEntry first, LayerTable tl, ErrRow er,
+                                           int s8, int t0, int lane, Pending pending)
 {
     if constexpr (R == 0) {
+        pending.settle();
         if (inplace)
             __syncthreads();
     } else {
         float best[R];
         unsigned arg[R];
-        sweep_group<R, kLevel>(prev, first, shifts_l, order_l, er, s8, t0, lane, best, arg);
+        sweep_group<R, kLevel>(prev, first, tl, er, s8, t0, lane, best, arg);
+        pending.settle();
         const int tl = t0 + lane;
 #pragma unroll
         for (int j = 0; j < R; ++j) {
@@ -488,15 +611,14 @@ __device__ __forceinline__ void fill_group(const float *prev, float *cur, uint8_
 
 template <bool kLevel, bool inplace>
 __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cur, uint8_t *choice,
-                                             float *rec, LevelEntry first,
-                                             const int32_t *shifts_l, const int32_t *order_l,
-                                             ErrRow er, int s8, int t0, int lane)
+                                             float *rec, LevelEntry first, LayerTable tl,
+                                             ErrRow er, int s8, int t0, int lane, Pending pending)
 {
     switch (r) {
 #define SPDY_CASE(RR)                                                                          \
     case RR:                                                                                   \
-        fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, shifts_l, order_l,      \
-                                        er, s8, t0, lane);                                     \
+        fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, tl, er, s8, t0, lane,   \
+                                        pending);                                              \
         break;
         SPDY_CASE(0)
         SPDY_CASE(1)
@@ -513,8 +635,8 @@ __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cu
 #define SPDY_CASE(RR)                                                                          \
     case RR:                                                                                   \
         if constexpr (!kLevel)                                                                 \
-            fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, shifts_l, order_l,  \
-                                            er, s8, t0, lane);                                 \
+            fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, tl, er, s8, t0,     \
+                                            lane, pending);                                    \
         break;
         SPDY_CASE(11)
         SPDY_CASE(12)
@@ -546,17 +668,20 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 //              (`path` 0: one candidate per workgroup, two rows of kHalo + pitch floats each)
 //   in place : a layer is swept, barrier, written back to the same row, barrier; otherwise two
 //              rows alternate with one barrier per layer
+//   kNarrow  : S <= 64, one lane per level: the next layer's table is loaded without dependent
+//              loads while a layer is swept (a separate instantiation, so that the waits of the
+//              two ways of loading do not meet in one control-flow join)
 // `pitch` is the record's row pitch (elements per (k, l) row).
-template <bool kLevel, bool kLds>
+template <bool kLevel, bool kLds, bool kNarrow>
 __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
-    ErrSource src, const int32_t *__restrict__ meta, const int32_t *__restrict__ shifts,
-    const int32_t *__restrict__ order, int path, int K, int L,
-    int S, int s8, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
+    ErrSource src, const int32_t *__restrict__ meta, LevelTables tables, int path, int K, int L,
+    int S, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
     float *__restrict__ rows, int32_t *__restrict__ tstar, float *__restrict__ cost, Resume resume)
 {
     extern __shared__ float lds[];
     __shared__ float s_best[kFillWaves];
     __shared__ int s_time[kFillWaves];
+    __shared__ float s_entries[2][kFillWaves][kWave];   // per team: merged errors, two layers
     if (meta[kMetaPath] != path)
         return;                                  // another launch does the work
     const int bp = meta[kMetaBudget];
@@ -618,13 +743,38 @@ __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
     if (resume.first_layer)
         __syncthreads();
 
-    // lane i keeps visited level i of the layer being swept; the next layer's is fetched early
-    LevelEntry next_first = load_level(shifts, order, src.row(ke, 0, L, S), s8, 0, lane);
+    // lane i keeps visited entry i of the layer being swept; the next layer's is fetched early
+    const int s8 = tables.s8;
+    constexpr bool kShared = kNarrow && !kLevel;  // merged errors go through the team's table
+    const bool producer = kShared && wv == 0 && team < teams;
+    float *table = &s_entries[0][team < teams ? team : 0][0];
+    LevelEntry next_first{INT32_MAX, 0.0f};
+    LevelFetch next_fetch{INT32_MAX, 0.0f, 0};
+    if constexpr (kNarrow) {
+        next_fetch = fetch_levels<kLevel>(tables.layer(0), src.row(ke, 0, L, S), S, s8, lane,
+                                          producer);
+        if (producer)
+            publish_entries(table, next_fetch, S, lane);
+        if constexpr (kShared)
+            __syncthreads();
+    } else {
+        next_first = load_level<kLevel>(tables.layer(0), src.row(ke, 0, L, S), s8, 0, lane);
+    }
+    Pending{&next_fetch, &next_first}.settle();   // no load is in flight at the loop's head
     for (int l = 0; l < L; ++l) {
-        const LevelEntry first = next_first;
-        if (l + 1 < L)
-            next_first = load_level(shifts + (size_t)(l + 1) * s8, order + (size_t)(l + 1) * s8,
-                                    src.row(ke, l + 1, L, S), s8, 0, lane);
+        LevelEntry first = next_first;
+        if constexpr (kNarrow) {
+            first.shift = next_fetch.shift;
+            first.err = kLevel ? next_fetch.raw : table[(l & 1) * kFillWaves * kWave + lane];
+        }
+        if (l + 1 < L) {
+            const LayerTable tn = tables.layer(l + 1);
+            const ErrRow en = src.row(ke, l + 1, L, S);
+            if constexpr (kNarrow)
+                next_fetch = fetch_levels<kLevel>(tn, en, S, s8, lane, producer);
+            else
+                next_first = load_level<kLevel>(tn, en, s8, 0, lane);
+        }
         const float *prev = (l & 1) ? buf1 : buf0;
         float *cur = (l & 1) ? buf0 : buf1;
         int c = 0, c_end = 0;
@@ -635,23 +785,26 @@ __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
         }
         uint8_t *choice_l = kLevel ? choice + ((size_t)k * L + l) * pitch : nullptr;
         float *drec_l = kLevel ? nullptr : drec + ((size_t)k * L + l) * pitch;
-        const int32_t *shifts_l = shifts + (size_t)l * s8;
-        const int32_t *order_l = order + (size_t)l * s8;
+        const LayerTable tl = tables.layer(l);
         const ErrRow er = src.row(ke, l, L, S);
         constexpr int kMax = kLevel ? kMaxGroupLevel : kMaxGroup;
+        const Pending pending{&next_fetch, &next_first};
         if (inplace) {                           // c_end - c <= kMax by construction
             fill_group_n<kLevel, true>(min(c_end - c, kMax), prev, cur, choice_l, drec_l, first,
-                                       shifts_l, order_l, er, s8, c * kWave, lane);
+                                       tl, er, s8, c * kWave, lane, pending);
         } else {
             while (c < c_end) {
                 const int n = c_end - c;
                 const int groups = (n + kMax - 1) / kMax;
                 const int r = (n + groups - 1) / groups;
-                fill_group_n<kLevel, false>(r, prev, cur, choice_l, drec_l, first, shifts_l,
-                                            order_l, er, s8, c * kWave, lane);
+                fill_group_n<kLevel, false>(r, prev, cur, choice_l, drec_l, first, tl, er, s8,
+                                            c * kWave, lane, pending);
                 c += r;
             }
         }
+        // the table of the next layer; the barrier that ends this layer publishes it
+        if (producer && l + 1 < L)
+            publish_entries(table + ((l + 1) & 1) * kFillWaves * kWave, next_fetch, S, lane);
         __syncthreads();
     }
 
@@ -901,13 +1054,15 @@ int launch_status()
     return hipGetLastError() == hipSuccess ? SPDY_DP_OK : SPDY_DP_ERR_LAUNCH;
 }
 
-template <bool kLevel>
+template <bool kLevel, bool kNarrow>
 int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume resume, int K, int L,
                 int S, int B, char *ws, float *cost, hipStream_t q)
 {
     int32_t *meta = reinterpret_cast<int32_t *>(ws + lay.meta_off);
     int32_t *shifts = reinterpret_cast<int32_t *>(ws + lay.shifts_off);
     int32_t *order = reinterpret_cast<int32_t *>(ws + lay.order_off);
+    int32_t *start = reinterpret_cast<int32_t *>(ws + lay.start_off);
+    int32_t *entry = reinterpret_cast<int32_t *>(ws + lay.entry_off);
     int32_t *tstar = reinterpret_cast<int32_t *>(ws + lay.tstar_off);
     uint8_t *choice = kLevel ? reinterpret_cast<uint8_t *>(ws + lay.record_off) : nullptr;
     float *drec = kLevel ? nullptr : reinterpret_cast<float *>(ws + lay.record_off);
@@ -930,8 +1085,8 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
         lds_small = kLdsHalf;
         lds_large = full_need <= (size_t)kLdsBytes ? (int)full_need : kLdsBytes;
     }
-    auto in_lds = dp_fill<kLevel, true>;
-    auto in_global = dp_fill<kLevel, false>;
+    auto in_lds = dp_fill<kLevel, true, kNarrow>;
+    auto in_global = dp_fill<kLevel, false, kNarrow>;
     const int lds_max = lds_large ? lds_large : lds_small;
     if (lds_max > 64 * 1024 &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(in_lds),
@@ -941,15 +1096,16 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
 
     hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, L, S, s8, B, waves,
                        kLevel ? kMaxGroupLevel : kMaxGroup, lds_small, lds_large, kLevel ? 0 : 1,
-                       meta, shifts, order);
-    hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, shifts, order,
-                       1, K, L, S, s8, pitch, choice, drec, rows, tstar, cost, resume);
+                       meta, shifts, order, start, entry);
+    const LevelTables tables{shifts, order, start, entry, s8};
+    hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, tables, 1, K,
+                       L, S, pitch, choice, drec, rows, tstar, cost, resume);
     if (lds_large)
-        hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, shifts,
-                           order, 2, K, L, S, s8, pitch, choice, drec, rows, tstar, cost, resume);
+        hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, tables,
+                           2, K, L, S, pitch, choice, drec, rows, tstar, cost, resume);
     if (lay.may_spill)
-        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, src, meta, shifts, order,
-                           0, K, L, S, s8, pitch, choice, drec, rows, tstar, cost, resume);
+        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, src, meta, tables, 0, K,
+                           L, S, pitch, choice, drec, rows, tstar, cost, resume);
     return launch_status();
 }
 
@@ -974,9 +1130,13 @@ int fill_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B, flo
     hipStream_t q = static_cast<hipStream_t>(stream);
     char *ws = static_cast<char *>(workspace);
     (void)hipGetLastError();
+    if (S <= kWave)
+        return lay.variant == kLevelRecord
+                   ? launch_fill<true, true>(lay, tau, src, resume, K, L, S, B, ws, cost, q)
+                   : launch_fill<false, true>(lay, tau, src, resume, K, L, S, B, ws, cost, q);
     return lay.variant == kLevelRecord
-               ? launch_fill<true>(lay, tau, src, resume, K, L, S, B, ws, cost, q)
-               : launch_fill<false>(lay, tau, src, resume, K, L, S, B, ws, cost, q);
+               ? launch_fill<true, false>(lay, tau, src, resume, K, L, S, B, ws, cost, q)
+               : launch_fill<false, false>(lay, tau, src, resume, K, L, S, B, ws, cost, q);
 }
 
 int backtrace_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B,

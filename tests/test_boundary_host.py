@@ -56,7 +56,8 @@ def test_workspace_size(binding):
     fast = binding.spdy_dp_workspace_bytes(K, L, S, B)
     small = binding.spdy_dp_workspace_bytes_min(K, L, S, B)
     # fp32 D per cell (one extra row per candidate) vs one byte per cell, rows padded to 64
-    tables = 2 * 4 * L * ((S + 7) // 8 * 8)     # visiting order and shifts per (layer, level)
+    # per (layer, level): shifts, visiting order, entry starts (8 more per layer), entry of a level
+    tables = 4 * 4 * L * ((S + 7) // 8 * 8) + 4 * 8 * L
     assert 4 * K * L * row + tables <= fast <= 4 * K * L * row + tables + 16384
     assert K * L * row + tables <= small <= K * L * row + tables + 16384
     lay = binding.spdy_dp_workspace_layout(K, L, S, B, fast)
