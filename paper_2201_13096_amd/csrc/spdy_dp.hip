@@ -36,10 +36,16 @@
 namespace {
 
 constexpr int kWave = 64;            // lanes per wavefront = buckets per chunk
-constexpr int kMaxGroup = 13;        // most chunks a wave keeps in registers at once (D record)
-constexpr int kMaxGroupLevel = 10;   // same when the level is tracked too (more registers each)
-constexpr int kFillThreads = 1024;
-constexpr int kFillWaves = kFillThreads / kWave;
+// The fill kernel's shape per record variant.  D record: 8 waves of up to 128 registers, each
+// keeping up to 26 chunks of a row (two workgroups, 16 waves, per compute unit): long sweeps
+// between the barriers of a layer.  Level record: 16 waves of up to 64 registers with up to 10
+// chunks each (value and level per chunk).
+constexpr int kMaxGroup = 26;        // most chunks a wave keeps in registers at once (D record)
+constexpr int kMaxGroupLevel = 10;   // same when the level is tracked too
+constexpr int kFillWaves = 8;        // waves of a fill workgroup (D record)
+constexpr int kFillWavesLevel = 16;  // (level record)
+constexpr int kMaxFillWaves = 16;
+template <bool kLevel> constexpr int fill_waves() { return kLevel ? kFillWavesLevel : kFillWaves; }
 constexpr int kWalkThreads = 256;    // D-record walk back: 4 waves = 4 candidates per workgroup
 constexpr int kLdsStatic = 8192 + 256;    // the fill kernel's static LDS (entry tables, argmin)
 constexpr int kLdsBytes = 160 * 1024 - kLdsStatic;       // dynamic LDS a workgroup can get
@@ -641,6 +647,19 @@ __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cu
         SPDY_CASE(11)
         SPDY_CASE(12)
         SPDY_CASE(13)
+        SPDY_CASE(14)
+        SPDY_CASE(15)
+        SPDY_CASE(16)
+        SPDY_CASE(17)
+        SPDY_CASE(18)
+        SPDY_CASE(19)
+        SPDY_CASE(20)
+        SPDY_CASE(21)
+        SPDY_CASE(22)
+        SPDY_CASE(23)
+        SPDY_CASE(24)
+        SPDY_CASE(25)
+        SPDY_CASE(26)
 #undef SPDY_CASE
     }
 }
@@ -673,15 +692,15 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 //              two ways of loading do not meet in one control-flow join)
 // `pitch` is the record's row pitch (elements per (k, l) row).
 template <bool kLevel, bool kLds, bool kNarrow>
-__global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
+__global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void dp_fill(
     ErrSource src, const int32_t *__restrict__ meta, LevelTables tables, int path, int K, int L,
     int S, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
     float *__restrict__ rows, int32_t *__restrict__ tstar, float *__restrict__ cost, Resume resume)
 {
     extern __shared__ float lds[];
-    __shared__ float s_best[kFillWaves];
-    __shared__ int s_time[kFillWaves];
-    __shared__ float s_entries[2][kFillWaves][kWave];   // per team: merged errors, two layers
+    __shared__ float s_best[kMaxFillWaves];
+    __shared__ int s_time[kMaxFillWaves];
+    __shared__ float s_entries[2][kMaxFillWaves][kWave];   // per team: merged errors, two layers
     if (meta[kMetaPath] != path)
         return;                                  // another launch does the work
     const int bp = meta[kMetaBudget];
@@ -765,7 +784,7 @@ __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
         LevelEntry first = next_first;
         if constexpr (kNarrow) {
             first.shift = next_fetch.shift;
-            first.err = kLevel ? next_fetch.raw : table[(l & 1) * kFillWaves * kWave + lane];
+            first.err = kLevel ? next_fetch.raw : table[(l & 1) * kMaxFillWaves * kWave + lane];
         }
         if (l + 1 < L) {
             const LayerTable tn = tables.layer(l + 1);
@@ -804,7 +823,7 @@ __global__ __launch_bounds__(kFillThreads, 8) void dp_fill(
         }
         // the table of the next layer; the barrier that ends this layer publishes it
         if (producer && l + 1 < L)
-            publish_entries(table + ((l + 1) & 1) * kFillWaves * kWave, next_fetch, S, lane);
+            publish_entries(table + ((l + 1) & 1) * kMaxFillWaves * kWave, next_fetch, S, lane);
         __syncthreads();
     }
 
@@ -1092,7 +1111,7 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
         hipFuncSetAttribute(reinterpret_cast<const void *>(in_lds),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_max) != hipSuccess)
         return SPDY_DP_ERR_LAUNCH;
-    const int waves = nchunks < kFillWaves ? nchunks : kFillWaves;
+    const int waves = nchunks < fill_waves<kLevel>() ? nchunks : fill_waves<kLevel>();
 
     hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, L, S, s8, B, waves,
                        kLevel ? kMaxGroupLevel : kMaxGroup, lds_small, lds_large, kLevel ? 0 : 1,

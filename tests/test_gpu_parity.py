@@ -84,7 +84,7 @@ def check_tables(dp, tau, err_k, B, ws, k, K):
     rec = ws[a:a + rows * pitch * esize].cpu().numpy()
     rec = rec.view(np.float32 if esize == 4 else np.uint8).reshape(rows, pitch)
     if meta[3] == 0:     # rows in global memory: the reduced rows (plus aprons) exceed LDS
-        assert 2 * (meta[2] + 832) * 4 > 160 * 1024 - 8448   # 8448 bytes of static LDS
+        assert 2 * (meta[2] + 1664) * 4 > 160 * 1024 - 8448   # apron 26 * 64, static LDS 8448
     for l in range(L):
         n = int(min(nact[l] * 64, bp + 1))
         want_D = D[l, lo[l]:lo[l] + n]
@@ -135,7 +135,7 @@ EDGE_SHAPES = [
     # K, L, S, B  (B + 1 deliberately not a multiple of 64 in most; several chunks per wave)
     (3, 1, 1, 0), (2, 1, 5, 7), (4, 5, 1, 100), (5, 6, 7, 63), (5, 6, 7, 64), (3, 9, 12, 1000),
     (7, 12, 33, 2500), (2, 4, 255, 700), (3, 17, 40, 10000), (2, 20, 16, 16384),
-    (2, 7, 9, 18559), (2, 6, 10, 18560),             # around the largest rows that fit LDS
+    (2, 7, 9, 17727), (2, 6, 10, 17728),             # around the largest rows that fit LDS
     (3, 6, 10, 20480), (2, 5, 12, 33000), (1, 4, 6, 70001),   # rows in global memory
     (2, 300, 3, 500),                                # more layers than prepare threads
     (2, 5, 64, 300), (2, 5, 65, 300), (3, 4, 129, 900),       # level-block boundaries
