@@ -55,6 +55,8 @@ constexpr int kBatch = 8;                 // level tables are padded to a multip
 constexpr unsigned kNoLevel = 0xFF;
 constexpr size_t kAlign = 256;
 constexpr int kMetaHeader = 8;       // int32 words before the per-layer arrays
+// meta: header | m_l [L] | chunks of row l [L] | chunk boundaries of the team waves [L][stride]
+constexpr int kRangeStride = kMaxFillWaves + 1;
 
 // kMetaPath: 0 = rows in global memory, 1 / 2 = rows in LDS, fill kernel launched with the
 // smaller / larger LDS allocation.  kMetaTeamWaves x kMetaTeams <= waves of a fill workgroup.
@@ -118,7 +120,8 @@ Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes)
     lay.may_spill = 2 * row_bytes > (size_t)kLdsBytes;
     lay.s8 = align_up((size_t)S, kBatch);
     lay.meta_off = 0;
-    lay.shifts_off = align_up((kMetaHeader + 2 * (size_t)L) * sizeof(int32_t), kAlign);
+    lay.shifts_off =
+        align_up((kMetaHeader + (2 + (size_t)kRangeStride) * L) * sizeof(int32_t), kAlign);
     lay.order_off = align_up(lay.shifts_off + (size_t)L * lay.s8 * sizeof(int32_t), kAlign);
     lay.start_off = align_up(lay.order_off + (size_t)L * lay.s8 * sizeof(int32_t), kAlign);
     lay.entry_off =
@@ -183,7 +186,7 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int L, int S, in
                                int32_t *__restrict__ meta)
 {
     __shared__ long long s_sum[8];
-    __shared__ int s_budget;
+    __shared__ int s_budget, s_team_waves;
     const int tid = threadIdx.x;
     int32_t *mn = meta + kMetaHeader;
     int32_t *nact = meta + kMetaHeader + L;
@@ -236,9 +239,11 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int L, int S, in
         meta[kMetaTeamWaves] = waves / teams;
         meta[kMetaInPlace] = inplace;
         s_budget = bp;
+        s_team_waves = waves / teams;
     }
     __syncthreads();
     const int bp = s_budget;
+    const int tw = s_team_waves;
     local = 0;
     for (int l = l0; l < l1; ++l) {
         int span = 0;
@@ -266,7 +271,12 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int L, int S, in
     for (int l = l0; l < l1; ++l) {
         h += nact[l];
         const long long top = h < bp ? h : bp;
-        nact[l] = bp < 0 ? 0 : (int)((top + kWave) / kWave);
+        const int n = bp < 0 ? 0 : (int)((top + kWave) / kWave);
+        nact[l] = n;
+        // wave w of a team sweeps chunks [w n / tw, (w + 1) n / tw) of this row
+        int32_t *range = meta + kMetaHeader + 2 * L + (size_t)l * kRangeStride;
+        for (int w = 0; w <= tw; ++w)
+            range[w] = (int)((long long)w * n / tw);
     }
 }
 
@@ -604,8 +614,8 @@ __device__ __forceinline__ void fill_group(const float *prev, float *cur, uint8_
         for (int j = 0; j < R; ++j) {
             if constexpr (kLevel)
                 choice[tl + j * kWave] = (uint8_t)arg[j];
-            else
-                rec[tl + j * kWave] = best[j];
+            else   // streamed: the record is not read again before the walk back
+                __builtin_nontemporal_store(best[j], &rec[tl + j * kWave]);
         }
         if (inplace)
             __syncthreads();
@@ -780,6 +790,8 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
         next_first = load_level<kLevel>(tables.layer(0), src.row(ke, 0, L, S), s8, 0, lane);
     }
     Pending{&next_fetch, &next_first}.settle();   // no load is in flight at the loop's head
+    const int32_t *range = meta + kMetaHeader + 2 * L + wv;   // chunk boundaries of this wave
+    int c_next = range[0], c_end_next = range[1];
     for (int l = 0; l < L; ++l) {
         LevelEntry first = next_first;
         if constexpr (kNarrow) {
@@ -796,11 +808,15 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
         }
         const float *prev = (l & 1) ? buf1 : buf0;
         float *cur = (l & 1) ? buf0 : buf1;
-        int c = 0, c_end = 0;
+        int c = 0, c_end = 0;                    // this wave's chunks of the row
         if (active && l >= l0) {
-            const int n = nact[l];               // chunks of this row that can be finite
-            c = (int)((long long)wv * n / tw);
-            c_end = (int)((long long)(wv + 1) * n / tw);
+            c = c_next;
+            c_end = c_end_next;
+        }
+        if (l + 1 < L) {                         // the next layer's, read a layer ahead
+            range += kRangeStride;
+            c_next = range[0];
+            c_end_next = range[1];
         }
         uint8_t *choice_l = kLevel ? choice + ((size_t)k * L + l) * pitch : nullptr;
         float *drec_l = kLevel ? nullptr : drec + ((size_t)k * L + l) * pitch;
