@@ -181,8 +181,8 @@ __device__ __forceinline__ long long block_scan_256(long long v, long long *part
 // reduced budget).  It also picks the path: which launch of the fill kernel (LDS allocation
 // lds_small or lds_large bytes, `waves` waves per workgroup) fits, into how many teams its waves
 // split, and whether one row per candidate is enough.  Thread i owns a slice of layers.
-__device__ void prepare_budget(const int32_t *__restrict__ tau, int L, int S, int B, int waves,
-                               int max_group, int lds_small, int lds_large,
+__device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots, int L, int S,
+                               int B, int waves, int max_group, int lds_small, int lds_large,
                                int32_t *__restrict__ meta)
 {
     __shared__ long long s_sum[8];
@@ -232,6 +232,11 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int L, int S, in
                 const long long fit = lds / team_lds;
                 if (teams > fit)
                     teams = (int)fit;
+                // with fewer candidates than the chip has room for, fewer candidates share a
+                // workgroup, so that each gets more waves and finishes sooner
+                const int spread = (K + slots - 1) / slots;
+                if (teams > spread)
+                    teams = spread;
             }
         }
         meta[kMetaPath] = path;
@@ -349,7 +354,8 @@ __device__ void prepare_order(const int32_t *__restrict__ tau, int l, int S, int
     }
 }
 
-__global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ tau, int L, int S,
+__global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ tau, int K,
+                                                  int slots, int L, int S,
                                                   int s8, int B, int waves, int max_group,
                                                   int lds_small, int lds_large, int sorted,
                                                   int32_t *__restrict__ meta,
@@ -359,7 +365,7 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
                                                   int32_t *__restrict__ entry_of)
 {
     if (blockIdx.x == 0)
-        prepare_budget(tau, L, S, B, waves, max_group, lds_small, lds_large, meta);
+        prepare_budget(tau, K, slots, L, S, B, waves, max_group, lds_small, lds_large, meta);
     else
         prepare_order(tau, blockIdx.x - 1, S, s8, sorted, shifts, order, start, entry_of);
 }
@@ -1129,7 +1135,14 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
         return SPDY_DP_ERR_LAUNCH;
     const int waves = nchunks < fill_waves<kLevel>() ? nchunks : fill_waves<kLevel>();
 
-    hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, L, S, s8, B, waves,
+    // workgroups the chip holds at once: two per compute unit for either variant
+    int device = 0, units = 0;
+    if (hipGetDevice(&device) != hipSuccess ||
+        hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess ||
+        units <= 0)
+        return SPDY_DP_ERR_LAUNCH;
+    hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, K, 2 * units, L, S, s8, B,
+                       waves,
                        kLevel ? kMaxGroupLevel : kMaxGroup, lds_small, lds_large, kLevel ? 0 : 1,
                        meta, shifts, order, start, entry);
     const LevelTables tables{shifts, order, start, entry, s8};

@@ -139,7 +139,10 @@ EDGE_SHAPES = [
     (3, 6, 10, 20480), (2, 5, 12, 33000), (1, 4, 6, 70001),   # rows in global memory
     (2, 300, 3, 500),                                # more layers than prepare threads
     (2, 5, 64, 300), (2, 5, 65, 300), (3, 4, 129, 900),       # level-block boundaries
-    (37, 4, 5, 200), (19, 3, 6, 1500),               # candidates not a multiple of the teams
+    (37, 4, 5, 200), (19, 3, 6, 1500),               # few candidates: one team per workgroup
+    # more candidates than the chip holds at once: several teams per workgroup, the last
+    # workgroup partly filled
+    (1100, 4, 5, 700), (2600, 3, 6, 1500), (4100, 3, 4, 500),
 ]
 
 
