@@ -19,13 +19,14 @@
 //     dwords (conflict-free for any shift) and every store of the record is 64 consecutive
 //     elements;
 //   * a wave keeps R chunks in registers (running minimum, and the level when tracked, for R
-//     buckets per lane) and sweeps the levels once; lane i holds the i-th level of the layer,
-//     one ballot finds the applicable levels and v_readlane moves shift and error to scalar
+//     buckets per lane) and sweeps the layer once; lane i holds the i-th entry of the layer
+//     (a level, or with the D record all levels of one shift, which one update serves),
+//     one ballot finds the applicable entries and v_readlane moves shift and error to scalar
 //     registers, so the sweep issues no memory instruction besides the LDS reads;
-//   * a workgroup of 16 waves is split at run time into teams, one candidate per team, so that
-//     each wave owns about ten chunks whatever the reduced row length is; when every wave holds
-//     all its chunks of the row in registers the row is updated in place (one row per
-//     candidate), otherwise two rows alternate.
+//   * the waves of a workgroup are split at run time into teams, one candidate per team, so
+//     that each wave owns as many chunks as its registers hold whatever the reduced row length
+//     is; when every wave holds all its chunks of the row in registers the row is updated in
+//     place (one row per candidate), otherwise two rows alternate.
 // When not even one reduced row fits in LDS the same kernel runs with the rows in global memory.
 #include <hip/hip_runtime.h>
 
