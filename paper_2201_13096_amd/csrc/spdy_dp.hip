@@ -1046,7 +1046,7 @@ __global__ __launch_bounds__(kWalkThreads) void dp_backtrace_values(
             u[b] = valid[b] ? (int)uu : 0;
             pv[b] = __builtin_inff();
             if (valid[b])
-                pv[b] = l > 0 ? prow[u[b]] : -0.0f;
+                pv[b] = l > 0 ? __builtin_nontemporal_load(&prow[u[b]]) : -0.0f;
         }
         if (l > 0)
             next = load_layer<kLevelBlocks>(tau, src.row(k, l - 1, L, S), meta, l - 1, L, S, lane);
