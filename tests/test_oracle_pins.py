@@ -417,3 +417,63 @@ def test_threaded_runner_equals_serial():
     p1, c1 = oracle.solve_ref(tau, err, B, threads=1)
     p4, c4 = oracle.solve_ref(tau, err, B, threads=4)
     assert (p1 == p4).all() and c1.tobytes() == c4.tobytes()
+
+
+# ------------------------------------------------------------------------------------------------
+# Facts about fp32 arithmetic and about Alg. 1 that the device design leans on; checked here on
+# the CPU with NumPy's IEEE fp32 and the oracle, so a violation shows up without a GPU.
+
+def test_rounded_add_is_monotone_so_equal_time_levels_fold():
+    """min_s fl(p + e_s) == fl(p + min_s e_s): levels of a layer that take the same time read the
+    same cell p of D_{l-1}, so one update with their smallest error serves them all."""
+    rng = np.random.default_rng(123)
+    scales = [2.0 ** k for k in (-149, -140, -126, -30, -1, 0, 10, 60, 120)]
+    for _ in range(400):
+        p = F32(rng.random() * rng.choice(scales))
+        if rng.random() < 0.1:
+            p = F32(np.inf)
+        e = (rng.random(7) * rng.choice(scales)).astype(F32)
+        if rng.random() < 0.3:
+            e[rng.integers(0, 7)] = F32(np.inf)
+        if rng.random() < 0.3:
+            e = np.where(np.isfinite(e), -e, e).astype(F32)   # negative finite errors are allowed
+        with np.errstate(over="ignore"):
+            each = np.array([F32(p + x) for x in e], dtype=F32)
+            folded = F32(p + e.min())
+        assert each.min() == folded                        # == : the sign of a zero may differ
+    # and adjacent fp32 values: the add cannot reorder them
+    x = F32(1.0)
+    for e_lo in (F32(2.0 ** -24), F32(2.0 ** -25), F32(0.0)):
+        e_hi = np.nextafter(e_lo, F32(1.0), dtype=F32)
+        assert F32(x + e_lo) <= F32(x + e_hi)
+
+
+def test_equal_time_levels_can_be_folded_in_alg1():
+    """Replacing the levels of one time by a single level carrying their smallest error changes
+    neither the optimal cost nor D anywhere (checked on the oracle's matrices)."""
+    rng = np.random.default_rng(5)
+    for _ in range(20):
+        L, S, B = 5, 8, 60
+        tau = rng.integers(0, 9, size=(L, S)).astype(np.int32)      # many equal times
+        err = rng.random((1, L, S)).astype(F32)
+        D, _, _, cost = oracle.tables_ref(tau, err, B)
+        tau2 = np.full_like(tau, B + 1)                              # unused slots never fit
+        err2 = np.full_like(err, np.inf)
+        for l in range(L):
+            for i, t in enumerate(np.unique(tau[l])):
+                tau2[l, i] = t
+                err2[0, l, i] = err[0, l][tau[l] == t].min()
+        D2, _, _, cost2 = oracle.tables_ref(tau2, err2, B)
+        assert np.array_equal(D, D2) and F32(cost) == F32(cost2)
+
+
+def test_rows_do_not_depend_on_later_layers():
+    """D_l is a function of layers 0..l only (Eq. 2): what lets a candidate that shares its first
+    layers with a solved one start from that one's row."""
+    rng = np.random.default_rng(6)
+    tau, err, B = workloads.random_instance(rng, 1, 7, 6, 90, integer_err=4)
+    D, _, _, _ = oracle.tables_ref(tau, err, B)
+    other = err.copy()
+    other[0, 4:] = rng.random((3, 6)).astype(F32)
+    D2, _, _, _ = oracle.tables_ref(tau, other, B)
+    assert np.array_equal(D[:4], D2[:4]) and not np.array_equal(D[4:], D2[4:])
