@@ -106,7 +106,7 @@ def check_tables(dp, tau, err_k, B, ws, k, K):
 # --------------------------------------------------------------------------- the five configs
 @pytest.mark.parametrize("compact", [False, True], ids=["d_record", "level_record"])
 @pytest.mark.parametrize("name", ["tiny", "rn50_k1", "rn50_k1024", "bert_k4096", "stress_k256",
-                                  "paper_rn50_k1024"])
+                                  "paper_rn50_k1024", "rn50_params_k1024"])
 def test_config_bit_exact(dp, name, compact, reference):
     cfg = workloads.CONFIGS[name]
     print(f"[parity] config {name}: K={cfg.K} L={cfg.L} S={cfg.S} B={cfg.B} "

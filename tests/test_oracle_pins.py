@@ -279,7 +279,7 @@ def test_integer_program_cross_check():
 
 
 # --------------------------------------------------------------------------- invariants
-@pytest.mark.parametrize("name", ["tiny", "rn50_k1", "paper_rn50_k1024"])
+@pytest.mark.parametrize("name", ["tiny", "rn50_k1", "paper_rn50_k1024", "rn50_params_k1024"])
 def test_invariants_on_benchmark_shaped_tables(name):
     cfg = workloads.CONFIGS[name]
     tau, err, B = workloads.generate(cfg, K=3)

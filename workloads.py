@@ -60,7 +60,28 @@ CONFIGS = {
     # grid of Sec. 4 "Setup", the error model of Eq. 4 and non-monotone timings (Sec. 3.1)
     "paper_rn50_k1024": Config("paper_rn50_k1024", K=1024, L=52, S=42, B=10000, q=0.0,
                                speedup=2.5, dense="lognormal", sigma=0.8, grid="paper"),
+    # another additive constraint (Sec. 3.1: the same problem with parameters or FLOPs in place of
+    # time): tau = remaining parameters of a ResNet-50's 53 convolutions and its classifier,
+    # budget = 1 / speedup of the dense parameter count
+    "rn50_params_k1024": Config("rn50_params_k1024", K=1024, L=54, S=40, B=10000, q=0.9,
+                                speedup=4.0, dense="rn50_params", sigma=0.0),
 }
+
+
+def resnet50_parameter_counts() -> np.ndarray:
+    """Weights of the 53 convolutions and the classifier of the standard ResNet-50 architecture
+    (7x7 stem, bottleneck stages of 3, 4, 6, 3 blocks with widths 64, 128, 256, 512 and a
+    1x1 projection in the first block of each stage, 2048 x 1000 classifier), in network order."""
+    counts = [7 * 7 * 3 * 64]
+    inplanes = 64
+    for width, blocks in ((64, 3), (128, 4), (256, 6), (512, 3)):
+        for b in range(blocks):
+            counts += [inplanes * width, 3 * 3 * width * width, width * 4 * width]
+            if b == 0:
+                counts.append(inplanes * 4 * width)
+            inplanes = 4 * width
+    counts.append(2048 * 1000)
+    return np.asarray(counts, dtype=np.float64)
 
 
 def level_grid(S: int, q: float) -> np.ndarray:
@@ -107,10 +128,14 @@ def generate(cfg: Config, seed: int = 0, K: int | None = None):
     elif cfg.dense == "bert":
         base = np.array([1.0, 1.0, 1.0, 1.0, 4.0, 4.0])[np.arange(cfg.L) % 6]
         d = base * rng.lognormal(0.0, cfg.sigma, size=cfg.L)
+    elif cfg.dense == "rn50_params":
+        d = resnet50_parameter_counts()
+        assert d.size == cfg.L
     else:
         raise ValueError(cfg.dense)
     p = level_grid(cfg.S, cfg.q)
-    f = 0.2 + 0.8 * np.power(1.0 - p, 1.5)
+    # time falls off slower than the kept fraction; a parameter count is exactly proportional
+    f = (1.0 - p) if cfg.dense == "rn50_params" else 0.2 + 0.8 * np.power(1.0 - p, 1.5)
     scale = cfg.speedup * cfg.B / d.sum()
     tau = np.floor(d[:, None] * f[None, :] * scale + 0.5).astype(np.int32)
     c = rng.random((K, cfg.L))
