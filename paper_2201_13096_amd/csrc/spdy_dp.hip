@@ -1114,27 +1114,26 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     const int s8 = (int)lay.s8;
 
     // The reduced row length is only known on the device, so the fill kernel is enqueued with an
-    // LDS allocation that lets two workgroups share a compute unit and, if the full budget could
-    // need more, once more with a larger one (and once with the rows in global memory if even
-    // that may not do); the prepare kernel picks the launch that fits and the others return at
-    // once.
-    const size_t full_need = 2 * (lay.row + kHalo) * sizeof(float);
-    int lds_small, lds_large;
-    if (full_need <= (size_t)kLdsHalf) {
-        lds_small = (int)full_need;
-        lds_large = 0;
-    } else {
-        lds_small = kLdsHalf;
-        lds_large = full_need <= (size_t)kLdsBytes ? (int)full_need : kLdsBytes;
-    }
+    // LDS allocation that lets two workgroups share a compute unit and, if a row of the full
+    // budget could need more, once more with a larger one (and once with the rows in global
+    // memory if even that may not do); the prepare kernel picks the launch that fits and the
+    // others return at once.  A row that the waves of a workgroup can hold in registers is
+    // updated in place whatever the reduced length turns out to be, so one row bounds the need;
+    // otherwise two rows alternate.
+    const int waves = nchunks < fill_waves<kLevel>() ? nchunks : fill_waves<kLevel>();
+    const int max_group = kLevel ? kMaxGroupLevel : kMaxGroup;
+    const size_t row_bytes = (lay.row + kHalo) * sizeof(float);
+    const size_t need = (long long)nchunks <= (long long)waves * max_group ? row_bytes : 2 * row_bytes;
+    const int lds_small = kLdsHalf;
+    const int lds_large = need <= (size_t)kLdsHalf ? 0
+                          : (need <= (size_t)kLdsBytes ? (int)need : kLdsBytes);
+    const bool in_memory = need > (size_t)kLdsBytes;      // implies lay.may_spill
     auto in_lds = dp_fill<kLevel, true, kNarrow>;
     auto in_global = dp_fill<kLevel, false, kNarrow>;
     const int lds_max = lds_large ? lds_large : lds_small;
-    if (lds_max > 64 * 1024 &&
-        hipFuncSetAttribute(reinterpret_cast<const void *>(in_lds),
+    if (hipFuncSetAttribute(reinterpret_cast<const void *>(in_lds),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_max) != hipSuccess)
         return SPDY_DP_ERR_LAUNCH;
-    const int waves = nchunks < fill_waves<kLevel>() ? nchunks : fill_waves<kLevel>();
 
     // workgroups the chip holds at once: two per compute unit for either variant
     int device = 0, units = 0;
@@ -1144,7 +1143,7 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
         return SPDY_DP_ERR_LAUNCH;
     hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, K, 2 * units, L, S, s8, B,
                        waves,
-                       kLevel ? kMaxGroupLevel : kMaxGroup, lds_small, lds_large, kLevel ? 0 : 1,
+                       max_group, lds_small, lds_large, kLevel ? 0 : 1,
                        meta, shifts, order, start, entry);
     const LevelTables tables{shifts, order, start, entry, s8};
     hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, tables, 1, K,
@@ -1152,7 +1151,7 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     if (lds_large)
         hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, tables,
                            2, K, L, S, pitch, choice, drec, rows, tstar, cost, resume);
-    if (lay.may_spill)
+    if (in_memory)
         hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, src, meta, tables, 0, K,
                            L, S, pitch, choice, drec, rows, tstar, cost, resume);
     return launch_status();
