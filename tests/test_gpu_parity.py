@@ -302,6 +302,7 @@ RESUME_SHAPES = [
     (12, 40, 30000, 9, 4000),
     (5, 12, 70000, 5, 20000),
     (7, 130, 5000, 11, 900),
+    (6, 5, 300, 1300, None),     # more candidates than workgroup slots: teams with different starts
 ]
 
 
