@@ -406,6 +406,20 @@ struct ErrSource {
         r.c_kl = err ? 0.0f : c[k * L + l];
         return r;
     }
+    // The same source seen from candidate k (its [L][S] table or its [L] sensitivities), so that
+    // a loop over the layers of one candidate does not redo the 64-bit index arithmetic.
+    __device__ __forceinline__ ErrSource of_candidate(size_t k, int L, int S) const
+    {
+        return ErrSource{err ? err + k * L * S : nullptr, c ? c + k * L : nullptr, w};
+    }
+    __device__ __forceinline__ ErrRow layer(int l, int S) const   // of a per-candidate view
+    {
+        ErrRow r;
+        r.err_kl = err ? err + (size_t)l * S : nullptr;
+        r.w = w;
+        r.c_kl = err ? 0.0f : c[l];
+        return r;
+    }
 };
 
 // Re-solving candidates that share their first layers with an already solved incumbent
@@ -779,6 +793,11 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     if (resume.first_layer)
         __syncthreads();
 
+    // this candidate's part of the inputs and of the record
+    const ErrSource mine = src.of_candidate(ke, L, S);
+    uint8_t *choice_k = kLevel ? choice + ke * L * pitch : nullptr;
+    float *drec_k = kLevel ? nullptr : drec + ke * L * pitch;
+
     // lane i keeps visited entry i of the layer being swept; the next layer's is fetched early
     const int s8 = tables.s8;
     constexpr bool kShared = kNarrow && !kLevel;  // merged errors go through the team's table
@@ -787,14 +806,14 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     LevelEntry next_first{INT32_MAX, 0.0f};
     LevelFetch next_fetch{INT32_MAX, 0.0f, 0};
     if constexpr (kNarrow) {
-        next_fetch = fetch_levels<kLevel>(tables.layer(0), src.row(ke, 0, L, S), S, s8, lane,
+        next_fetch = fetch_levels<kLevel>(tables.layer(0), mine.layer(0, S), S, s8, lane,
                                           producer);
         if (producer)
             publish_entries(table, next_fetch, S, lane);
         if constexpr (kShared)
             __syncthreads();
     } else {
-        next_first = load_level<kLevel>(tables.layer(0), src.row(ke, 0, L, S), s8, 0, lane);
+        next_first = load_level<kLevel>(tables.layer(0), mine.layer(0, S), s8, 0, lane);
     }
     Pending{&next_fetch, &next_first}.settle();   // no load is in flight at the loop's head
     const int32_t *range = meta + kMetaHeader + 2 * L + wv;   // chunk boundaries of this wave
@@ -807,7 +826,7 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
         }
         if (l + 1 < L) {
             const LayerTable tn = tables.layer(l + 1);
-            const ErrRow en = src.row(ke, l + 1, L, S);
+            const ErrRow en = mine.layer(l + 1, S);
             if constexpr (kNarrow)
                 next_fetch = fetch_levels<kLevel>(tn, en, S, s8, lane, producer);
             else
@@ -825,10 +844,10 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
             c_next = range[0];
             c_end_next = range[1];
         }
-        uint8_t *choice_l = kLevel ? choice + ((size_t)k * L + l) * pitch : nullptr;
-        float *drec_l = kLevel ? nullptr : drec + ((size_t)k * L + l) * pitch;
+        uint8_t *choice_l = kLevel ? choice_k + (size_t)l * pitch : nullptr;
+        float *drec_l = kLevel ? nullptr : drec_k + (size_t)l * pitch;
         const LayerTable tl = tables.layer(l);
-        const ErrRow er = src.row(ke, l, L, S);
+        const ErrRow er = mine.layer(l, S);
         constexpr int kMax = kLevel ? kMaxGroupLevel : kMaxGroup;
         const Pending pending{&next_fetch, &next_first};
         if (inplace) {                           // c_end - c <= kMax by construction
