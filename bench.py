@@ -59,8 +59,10 @@ def executed_updates_per_candidate(tau: np.ndarray, B: int, merge_equal_times: b
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
+    # the chip needs some tens of milliseconds of load to settle its clocks: with 3 warm-up and
+    # 20 timed steps of 0.6 ms the step reads 8 % longer than in steady state
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="rn50_k1024")
     ap.add_argument("--record", choices=["d", "level"], default="d",
                     help="what the fill records per cell: fp32 D (fast) or the one-byte level")
@@ -70,6 +72,9 @@ def main() -> int:
                     help="time spdy_dp_solve_from_incumbent instead: every candidate is candidate 0 "
                          "with D random layers resampled (one round of the search of Sec. 3.3), "
                          "sorted by its first resampled layer")
+    ap.add_argument("--overlap", action="store_true",
+                    help="pipeline consecutive steps over two streams and two workspaces: the "
+                         "walk back of step i runs beside the fill of step i + 1")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for "
@@ -122,7 +127,34 @@ def main() -> int:
         inc_ws = dp.alloc_workspace(1, L, S, B, dev)
         dp.spdy_dp_solve_batched(tau_d, torch.from_numpy(incumbent).to(dev), B, workspace=inc_ws)
 
+    if args.overlap:
+        if first_layer is not None:
+            print("bench.py: --overlap and --from-incumbent exclude each other", file=sys.stderr)
+            return 2
+        fill_stream, walk_stream = torch.cuda.Stream(), torch.cuda.Stream()
+        slots = [(ws, profile, cost),
+                 (dp.alloc_workspace(K, L, S, B, dev, compact=(args.record == "level")),
+                  torch.empty_like(profile), torch.empty_like(cost))]
+        walked = [None, None]                 # event: the walk back that last used the slot
+        turn = [0]
+
     def step(ev_a=None, ev_b=None):
+        if args.overlap:
+            i = turn[0] % 2
+            turn[0] += 1
+            ws_i, profile_i, cost_i = slots[i]
+            if walked[i] is not None:
+                fill_stream.wait_event(walked[i])
+            if ev_a is not None:
+                ev_a.record(fill_stream)
+            dp.spdy_dp_fill(tau_d, err_d, B, cost_i, ws_i, stream=fill_stream)
+            filled = ev_b if ev_b is not None else torch.cuda.Event()
+            filled.record(fill_stream)
+            walk_stream.wait_event(filled)
+            dp.spdy_dp_backtrace(tau_d, err_d, B, profile_i, cost_i, ws_i, stream=walk_stream)
+            walked[i] = torch.cuda.Event()
+            walked[i].record(walk_stream)
+            return
         if first_layer is not None:           # one fused call: no event between its stages
             if ev_a is not None:
                 ev_a.record()
@@ -149,8 +181,10 @@ def main() -> int:
         step()
     torch.cuda.synchronize()
 
+    # HIP events around the fill stage of every fourth timed step (an event pair costs about as
+    # much as a kernel launch, which shows on a 0.6 ms step)
     evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-           for _ in range(args.steps)]
+           if i % 4 == 0 else (None, None) for i in range(args.steps)]
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for a, b in evs:
@@ -158,7 +192,7 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    fill_ms = float(np.mean([a.elapsed_time(b) for a, b in evs]))
+    fill_ms = float(np.mean([a.elapsed_time(b) for a, b in evs if a is not None]))
 
     nominal = K * L * S * B
     executed = K * executed_updates_per_candidate(tau, B, args.record == "d")
@@ -184,7 +218,8 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "f32",
         "data": "synthetic",
-        "config": {"workload": cfg.name, "K": K, "L": L, "S": S, "B": B, "record": args.record,
+        "config": {"workload": cfg.name + ("+overlap" if args.overlap else ""),
+                   "K": K, "L": L, "S": S, "B": B, "record": args.record,
                    "executed_updates": executed, "nominal_updates": nominal},
         "roofline": {
             "bound": "alu",
