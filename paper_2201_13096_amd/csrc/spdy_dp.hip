@@ -78,7 +78,7 @@ struct Layout {
     size_t row;          // buckets per padded row for the full budget (multiple of 64)
     bool may_spill;      // rows of the full budget may exceed LDS: the global-row launch is needed
     size_t s8;           // levels per layer padded to a multiple of kBatch
-    size_t meta_off;     // int32 meta[kMetaHeader + 2 L]
+    size_t meta_off;     // int32 meta[kMetaHeader + (2 + kRangeStride) L]
     size_t shifts_off;   // int32 shifts[L][s8]: tau - m_l of the r-th visited entry
     size_t order_off;    // int32 order[L][s8]: level index at position r of the visiting order
     size_t start_off;    // int32 start[L][s8 + kBatch]: first position of entry r (D record)
