@@ -372,6 +372,29 @@ def test_resume_from_an_infeasible_incumbent(dp):
         assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, f"B={B}")
 
 
+def test_one_workspace_reused_across_different_problems(dp):
+    """Nothing a call leaves in the workspace may matter to the next one, whatever its shape."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(77)
+    shapes = [(5, 9, 12, 1000), (3, 4, 70, 900), (40, 3, 5, 200), (2, 12, 33, 2500), (6, 2, 3, 50),
+              (3, 9, 12, 1000)]
+    big = max(dp.spdy_dp_workspace_bytes(*sh) for sh in shapes)
+    ws = torch.empty(big, dtype=torch.uint8, device=dev)
+    ws.fill_(0x5A)
+    for i, (K, L, S, B) in enumerate(shapes):
+        tau, err, _ = workloads.random_instance(rng, K, L, S, B, tau_max=max(1, B // L),
+                                                integer_err=3 if i % 2 else None,
+                                                zero_tau_frac=0.1)
+        p_ref, c_ref = oracle.solve_ref(tau, err, B)
+        for nbytes in (big, dp.spdy_dp_workspace_bytes_min(K, L, S, B)):   # D record, level record
+            profile, cost = dp.spdy_dp_solve_batched(torch.from_numpy(tau).to(dev),
+                                                     torch.from_numpy(err).to(dev), B,
+                                                     workspace=ws[:nbytes])
+            torch.cuda.synchronize()
+            assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref,
+                        f"problem {i} {(K, L, S, B)} bytes {nbytes}")
+
+
 def test_workspace_too_small_is_an_error(dp):
     dev = torch.device("cuda:0")
     tau = torch.ones((2, 2), dtype=torch.int32, device=dev)
