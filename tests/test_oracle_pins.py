@@ -477,3 +477,47 @@ def test_rows_do_not_depend_on_later_layers():
     other[0, 4:] = rng.random((3, 6)).astype(F32)
     D2, _, _, _ = oracle.tables_ref(tau, other, B)
     assert np.array_equal(D[:4], D2[:4]) and not np.array_equal(D[4:], D2[4:])
+
+
+def test_reduced_table_equals_alg1_on_the_cells_that_matter():
+    """The exact reductions the device design rests on, replayed in NumPy against the oracle's
+    matrix: subtract each layer's smallest time m_l (budget B - M, row l shifted by m_0 + .. + m_l),
+    cut rows at the largest reachable reduced time, fold levels of equal time.  Every reduced cell
+    must equal Alg. 1's D at the shifted time, cells beyond the reach bound must be +inf there, and
+    the final argmin must pick the same (cost, t)."""
+    rng = np.random.default_rng(99)
+    for case in range(25):
+        L, S = int(rng.integers(1, 7)), int(rng.integers(1, 9))
+        B = int(rng.integers(0, 120))
+        tau, err, _ = workloads.random_instance(
+            rng, 1, L, S, B, tau_max=max(1, B // 2), integer_err=3 if case % 3 == 0 else None,
+            zero_tau_frac=0.15, over_budget_frac=0.1, layer_floor=B // (2 * L) if case % 2 else 0)
+        D, _, _, cost = oracle.tables_ref(tau, err, B)
+        m = tau.min(axis=1).astype(np.int64)
+        bp = B - int(m.sum())
+        if bp < 0:
+            assert np.isinf(cost)
+            continue
+        lo = np.cumsum(m)
+        prev = np.full(bp + 1, np.inf, dtype=F32)
+        prev[0] = F32(-0.0)                       # D before the first layer: time 0 costs nothing
+        reach = 0
+        for l in range(L):
+            shift = tau[l].astype(np.int64) - m[l]
+            usable = shift[shift <= bp]
+            reach = min(reach + int(usable.max()), bp)
+            cur = np.full(bp + 1, np.inf, dtype=F32)
+            for d in np.unique(usable):           # one update per distinct time, smallest error
+                e = err[0, l][shift == d].min()
+                with np.errstate(invalid="ignore"):
+                    cand = (prev[:bp + 1 - d] + e).astype(F32)
+                cur[d:] = np.minimum(cur[d:], cand)
+            assert np.isinf(cur[reach + 1:]).all()
+            want = D[l, lo[l]:lo[l] + bp + 1]
+            assert np.array_equal(cur, want), f"case {case} layer {l}"
+            assert np.isinf(D[l, :lo[l]]).all()   # below the shifted origin nothing is reachable
+            prev = cur
+        t_red = int(np.argmin(prev))
+        assert F32(prev[t_red]) == F32(cost) or (np.isinf(cost) and np.isinf(prev[t_red]))
+        if np.isfinite(cost):
+            assert t_red + int(m.sum()) == int(np.argmin(D[L - 1]))
