@@ -72,6 +72,9 @@ def main() -> int:
                     help="time spdy_dp_solve_from_incumbent instead: every candidate is candidate 0 "
                          "with D random layers resampled (one round of the search of Sec. 3.3), "
                          "sorted by its first resampled layer")
+    ap.add_argument("--checkpoints", type=int, default=None, metavar="STRIDE",
+                    help="time spdy_dp_solve_checkpointed instead (0: stride about sqrt(L)): a "
+                         "record of about 2 sqrt(L) rows per candidate, two fills")
     ap.add_argument("--overlap", action="store_true",
                     help="pipeline consecutive steps over two streams and two workspaces: the "
                          "walk back of step i runs beside the fill of step i + 1")
@@ -118,7 +121,15 @@ def main() -> int:
         first_layer = np.ascontiguousarray(first_layer[by_first])
     tau_d = torch.from_numpy(tau).to(dev)
     err_d = torch.from_numpy(err).to(dev)
-    ws = dp.alloc_workspace(K, L, S, B, dev, compact=(args.record == "level"))
+    if args.checkpoints is not None:
+        if args.record != "d" or args.from_incumbent > 0 or args.overlap:
+            print("bench.py: --checkpoints goes with the D record only, and with neither "
+                  "--from-incumbent nor --overlap", file=sys.stderr)
+            return 2
+        ws = torch.empty(dp.spdy_dp_workspace_bytes_checkpointed(K, L, S, B, args.checkpoints),
+                         dtype=torch.uint8, device=dev)
+    else:
+        ws = dp.alloc_workspace(K, L, S, B, dev, compact=(args.record == "level"))
     profile = torch.empty((K, L), dtype=torch.int16, device=dev)
     cost = torch.empty((K,), dtype=torch.float32, device=dev)
 
@@ -139,6 +150,13 @@ def main() -> int:
         turn = [0]
 
     def step(ev_a=None, ev_b=None):
+        if args.checkpoints is not None:      # one call, several fills: no single fill stage
+            if ev_a is not None:
+                ev_a.record()
+            dp.spdy_dp_solve_checkpointed(tau_d, err_d, B, args.checkpoints, profile, cost, ws)
+            if ev_b is not None:
+                ev_b.record()
+            return
         if args.overlap:
             i = turn[0] % 2
             turn[0] += 1
@@ -264,6 +282,11 @@ def main() -> int:
         }
         out["parity"] = bool((p_gpu[:n] == p_ref).all() and
                              (c_gpu[:n].view(np.uint32) == c_ref.view(np.uint32)).all())
+    if args.checkpoints is not None:
+        del out["roofline"], out["roofline_lds"]
+        out["config"]["workload"] = f"{cfg.name}+checkpoints(stride={args.checkpoints})"
+        out["config"]["workspace_bytes"] = int(ws.numel())
+        out["config"]["workspace_bytes_full_record"] = int(dp.spdy_dp_workspace_bytes(K, L, S, B))
     if first_layer is not None:
         # the roofline objects describe the plain fill; here the event pair spans the whole call
         # and a varying part of the updates is skipped

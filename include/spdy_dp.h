@@ -151,6 +151,21 @@ int spdy_dp_solve_from_incumbent(const int32_t *tau, const float *err, const int
                                  size_t incumbent_bytes, int16_t *profile, float *cost,
                                  void *workspace, size_t workspace_bytes, void *stream);
 
+/* The same solve with a fraction of the record.  Sec. 3.2 gives the dynamic program O(L T)
+ * memory for its matrices; this variant keeps about 2 sqrt(L) rows of D per candidate instead
+ * of L and pays with a second fill: a first pass over all layers keeps every stride-th row
+ * (checkpoints) and finds the final time, then each block of `stride` layers, the last one
+ * first, is filled again from the checkpoint below it and walked back.  Results equal
+ * spdy_dp_solve_batched bit for bit.
+ *   stride   layers per block; <= 0 picks ceil(sqrt(L)); values above L act as L
+ * Workspace: spdy_dp_workspace_bytes_checkpointed(K, L, S, B, stride) bytes with the SAME stride
+ * (about 4 * K * (L / stride + stride) * (B + 1)); a smaller one returns SPDY_DP_ERR_WORKSPACE.
+ * Everything else is as for spdy_dp_solve_batched. */
+size_t spdy_dp_workspace_bytes_checkpointed(int K, int L, int S, int B, int stride);
+int spdy_dp_solve_checkpointed(const int32_t *tau, const float *err, int K, int L, int S, int B,
+                               int stride, int16_t *profile, float *cost, void *workspace,
+                               size_t workspace_bytes, void *stream);
+
 /* Test/debug accessor: where things are in a workspace of `workspace_bytes` bytes.
  *   out[0] variant: 0 = fp32 D record, 1 = one-byte level record
  *   out[1] byte offset of the int32 header: [0] B - M (or -1 if M > B: nobody is feasible),

@@ -19,7 +19,8 @@ ERR_NULL, ERR_DIM, ERR_LEVELS, ERR_WORKSPACE, ERR_OVERFLOW, ERR_LAUNCH = -1, -2,
 
 EXPORTS = ("spdy_dp_workspace_bytes", "spdy_dp_workspace_bytes_min", "spdy_dp_solve_batched",
            "spdy_dp_solve_sensitivities", "spdy_dp_solve_budgets",
-           "spdy_dp_solve_from_incumbent", "spdy_dp_fill", "spdy_dp_backtrace",
+           "spdy_dp_solve_from_incumbent", "spdy_dp_workspace_bytes_checkpointed",
+           "spdy_dp_solve_checkpointed", "spdy_dp_fill", "spdy_dp_backtrace",
            "spdy_dp_workspace_layout", "spdy_dp_strerror")
 
 
@@ -53,6 +54,10 @@ def lib() -> ctypes.CDLL:
         L.spdy_dp_solve_from_incumbent.restype = i
         L.spdy_dp_solve_from_incumbent.argtypes = [vp, vp, vp, i, i, i, i, vp, sz, vp, vp, vp, sz,
                                                    vp]
+        L.spdy_dp_workspace_bytes_checkpointed.restype = sz
+        L.spdy_dp_workspace_bytes_checkpointed.argtypes = [i, i, i, i, i]
+        L.spdy_dp_solve_checkpointed.restype = i
+        L.spdy_dp_solve_checkpointed.argtypes = [vp, vp, i, i, i, i, i, vp, vp, vp, sz, vp]
         L.spdy_dp_fill.restype = i
         L.spdy_dp_fill.argtypes = [vp, vp, i, i, i, i, vp, vp, sz, vp]
         L.spdy_dp_backtrace.restype = i
@@ -222,6 +227,37 @@ def spdy_dp_solve_from_incumbent(tau, err, first_layer, B: int, incumbent_worksp
         tau.data_ptr(), err.data_ptr(), first_layer.data_ptr(), K, L, S, int(B),
         incumbent_workspace.data_ptr(), incumbent_workspace.numel(), profile.data_ptr(),
         cost.data_ptr(), workspace.data_ptr(), workspace.numel(), _stream(stream))
+    if st != OK:
+        raise SpdyDpError(st)
+    return profile, cost
+
+
+def spdy_dp_workspace_bytes_checkpointed(K: int, L: int, S: int, B: int, stride: int = 0) -> int:
+    return int(lib().spdy_dp_workspace_bytes_checkpointed(K, L, S, B, stride))
+
+
+def spdy_dp_solve_checkpointed(tau, err, B: int, stride: int = 0, profile=None, cost=None,
+                               workspace=None, stream=None):
+    """Alg. 1 with about 2 sqrt(L) rows of record per candidate (two fills)."""
+    tau = _dev(tau, torch.int32, "tau")
+    err = _dev(err, torch.float32, "err")
+    K, L, S = _shapes(tau, err)
+    if profile is None:
+        profile = torch.empty((K, L), dtype=torch.int16, device=err.device)
+    if cost is None:
+        cost = torch.empty((K,), dtype=torch.float32, device=err.device)
+    if workspace is None:
+        n = spdy_dp_workspace_bytes_checkpointed(K, L, S, B, stride)
+        if n == 0:
+            raise SpdyDpError(lib().spdy_dp_solve_checkpointed(None, None, K, L, S, int(B), stride,
+                                                               None, None, None, 0, None))
+        workspace = torch.empty(n, dtype=torch.uint8, device=err.device)
+    _dev(profile, torch.int16, "profile")
+    _dev(cost, torch.float32, "cost")
+    _dev(workspace, torch.uint8, "workspace")
+    st = lib().spdy_dp_solve_checkpointed(tau.data_ptr(), err.data_ptr(), K, L, S, int(B),
+                                          int(stride), profile.data_ptr(), cost.data_ptr(),
+                                          workspace.data_ptr(), workspace.numel(), _stream(stream))
     if st != OK:
         raise SpdyDpError(st)
     return profile, cost

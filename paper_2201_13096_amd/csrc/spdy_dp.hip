@@ -93,8 +93,9 @@ struct Layout {
 
 inline size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-// `workspace_bytes` selects the variant; pass SIZE_MAX to get the sizes only.
-Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes)
+// `workspace_bytes` selects the variant; pass SIZE_MAX to get the sizes only.  `rec_rows`: rows
+// of the record per candidate (L, or fewer for the solve with checkpoints).
+Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes, long long rec_rows = -1)
 {
     Layout lay{};
     if (K <= 0 || L <= 0 || S <= 0 || B < 0) {
@@ -130,8 +131,9 @@ Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes)
     lay.tstar_off = align_up(lay.entry_off + (size_t)L * lay.s8 * sizeof(int32_t), kAlign);
     lay.record_off = align_up(lay.tstar_off + (size_t)K * sizeof(int32_t), kAlign);
     const size_t rows = lay.may_spill ? 2 * (size_t)K * row_bytes : 0;
-    lay.rows_value = align_up(lay.record_off + (size_t)K * L * lay.row * sizeof(float), kAlign);
-    lay.rows_level = align_up(lay.record_off + (size_t)K * L * lay.row, kAlign);
+    const size_t nrec = rec_rows < 0 ? (size_t)L : (size_t)rec_rows;
+    lay.rows_value = align_up(lay.record_off + (size_t)K * nrec * lay.row * sizeof(float), kAlign);
+    lay.rows_level = align_up(lay.record_off + (size_t)K * nrec * lay.row, kAlign);
     lay.total_value = lay.rows_value + rows;
     lay.total_level = lay.rows_level + rows;
     if (workspace_bytes >= lay.total_value)
@@ -438,6 +440,24 @@ struct Resume {
     }
 };
 
+// Solving with a fraction of the record (Sec. 3.2 counts O(L T) memory for the matrices): a
+// first pass over all layers keeps only every `stride`-th row of D (checkpoints) and finds the
+// final time; then, from the last block of `stride` layers to the first, the block's rows are
+// filled again from the checkpoint below it into a small block record and walked back.
+//   pass 0 (checkpoints): layers [0, L); row l is kept at slot (l + 1) / stride - 1 when
+//                         (l + 1) is a multiple of stride and l + 1 < L
+//   pass 1 (one block)  : layers [begin, end), starting from checkpoint slot begin / stride - 1
+//                         (from scratch when begin = 0); row l is kept at slot l - begin of the
+//                         block record; no final argmin
+struct Blocks {
+    int pass;
+    int begin, end;
+    int stride;
+    int slots;                    // checkpoint rows per candidate
+    float *ckpt;                  // [K][slots][pitch]
+    float *block;                 // [K][stride][pitch]
+};
+
 struct LevelEntry {   // one visited level of one layer of one candidate
     int32_t shift;    // tau - m_l (INT32_MAX in padding entries)
     float err;
@@ -635,7 +655,7 @@ __device__ __forceinline__ void fill_group(const float *prev, float *cur, uint8_
         for (int j = 0; j < R; ++j) {
             if constexpr (kLevel)
                 choice[tl + j * kWave] = (uint8_t)arg[j];
-            else   // streamed: the record is not read again before the walk back
+            else if (rec)   // streamed: the record is not read again before the walk back
                 __builtin_nontemporal_store(best[j], &rec[tl + j * kWave]);
         }
         if (inplace)
@@ -721,12 +741,15 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 //   kNarrow  : S <= 64, one lane per level: the next layer's table is loaded without dependent
 //              loads while a layer is swept (a separate instantiation, so that the waits of the
 //              two ways of loading do not meet in one control-flow join)
+//   kBlocks  : the checkpoint / block passes of the small-record solve (D record only); the
+//              plain instantiation ignores `blocks`
 // `pitch` is the record's row pitch (elements per (k, l) row).
-template <bool kLevel, bool kLds, bool kNarrow>
+template <bool kLevel, bool kLds, bool kNarrow, bool kBlocks>
 __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void dp_fill(
     ErrSource src, const int32_t *__restrict__ meta, LevelTables tables, int path, int K, int L,
     int S, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
-    float *__restrict__ rows, int32_t *__restrict__ tstar, float *__restrict__ cost, Resume resume)
+    float *__restrict__ rows, int32_t *__restrict__ tstar, float *__restrict__ cost, Resume resume,
+    Blocks blocks)
 {
     extern __shared__ float lds[];
     __shared__ float s_best[kMaxFillWaves];
@@ -737,7 +760,7 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     const int bp = meta[kMetaBudget];
     const int tid = threadIdx.x, nthreads = blockDim.x;
     if (bp < 0) {                                // even the fastest levels exceed the budget
-        if (tid == 0)
+        if (tid == 0 && !(kBlocks && blocks.pass == 1))
             write_result(__builtin_inff(), 0, blockIdx.x, tstar, cost);
         return;
     }
@@ -792,11 +815,31 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     }
     if (resume.first_layer)
         __syncthreads();
+    // a block pass starts from the checkpoint below the block
+    const int lb = kBlocks ? blocks.begin : 0;   // layers [lb, le) are filled
+    const int le = kBlocks ? blocks.end : L;
+    if constexpr (kBlocks) {
+        if (lb > 0) {
+            float *dst = (lb & 1) ? buf1 : buf0;
+            const float *from =
+                blocks.ckpt + (ke * blocks.slots + (size_t)(lb / blocks.stride - 1)) * pitch;
+            const int n = nact[lb - 1] * kWave;
+            if (active)
+                for (int t = wv * kWave + lane; t < n; t += tw * kWave)
+                    dst[t] = from[t];
+            if (active && wv == 0 && lane == 0 && dst != buf0)
+                buf0[0] = __builtin_inff();      // undo the layer-0 start value
+            __syncthreads();
+        }
+    }
 
     // this candidate's part of the inputs and of the record
     const ErrSource mine = src.of_candidate(ke, L, S);
     uint8_t *choice_k = kLevel ? choice + ke * L * pitch : nullptr;
     float *drec_k = kLevel ? nullptr : drec + ke * L * pitch;
+    if constexpr (kBlocks)
+        drec_k = blocks.pass == 0 ? blocks.ckpt + ke * blocks.slots * pitch
+                                  : blocks.block + ke * blocks.stride * pitch;
 
     // lane i keeps visited entry i of the layer being swept; the next layer's is fetched early
     const int s8 = tables.s8;
@@ -806,25 +849,26 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     LevelEntry next_first{INT32_MAX, 0.0f};
     LevelFetch next_fetch{INT32_MAX, 0.0f, 0};
     if constexpr (kNarrow) {
-        next_fetch = fetch_levels<kLevel>(tables.layer(0), mine.layer(0, S), S, s8, lane,
+        next_fetch = fetch_levels<kLevel>(tables.layer(lb), mine.layer(lb, S), S, s8, lane,
                                           producer);
         if (producer)
-            publish_entries(table, next_fetch, S, lane);
+            publish_entries(table + (lb & 1) * kMaxFillWaves * kWave, next_fetch, S, lane);
         if constexpr (kShared)
             __syncthreads();
     } else {
-        next_first = load_level<kLevel>(tables.layer(0), mine.layer(0, S), s8, 0, lane);
+        next_first = load_level<kLevel>(tables.layer(lb), mine.layer(lb, S), s8, 0, lane);
     }
     Pending{&next_fetch, &next_first}.settle();   // no load is in flight at the loop's head
-    const int32_t *range = meta + kMetaHeader + 2 * L + wv;   // chunk boundaries of this wave
+    // chunk boundaries of this wave
+    const int32_t *range = meta + kMetaHeader + 2 * L + (size_t)lb * kRangeStride + wv;
     int c_next = range[0], c_end_next = range[1];
-    for (int l = 0; l < L; ++l) {
+    for (int l = lb; l < le; ++l) {
         LevelEntry first = next_first;
         if constexpr (kNarrow) {
             first.shift = next_fetch.shift;
             first.err = kLevel ? next_fetch.raw : table[(l & 1) * kMaxFillWaves * kWave + lane];
         }
-        if (l + 1 < L) {
+        if (l + 1 < le) {
             const LayerTable tn = tables.layer(l + 1);
             const ErrRow en = mine.layer(l + 1, S);
             if constexpr (kNarrow)
@@ -839,13 +883,23 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
             c = c_next;
             c_end = c_end_next;
         }
-        if (l + 1 < L) {                         // the next layer's, read a layer ahead
+        if (l + 1 < le) {                        // the next layer's, read a layer ahead
             range += kRangeStride;
             c_next = range[0];
             c_end_next = range[1];
         }
         uint8_t *choice_l = kLevel ? choice_k + (size_t)l * pitch : nullptr;
         float *drec_l = kLevel ? nullptr : drec_k + (size_t)l * pitch;
+        if constexpr (kBlocks) {
+            if (blocks.pass == 1)
+                drec_l = drec_k + (size_t)(l - lb) * pitch;
+            else if ((l + 1) % blocks.stride == 0 && l + 1 < L)
+                drec_l = drec_k + (size_t)((l + 1) / blocks.stride - 1) * pitch;
+            else
+                drec_l = nullptr;                // this row is not kept
+        } else if constexpr (!kLevel) {
+            __builtin_assume(drec_l != nullptr);
+        }
         const LayerTable tl = tables.layer(l);
         const ErrRow er = mine.layer(l, S);
         constexpr int kMax = kLevel ? kMaxGroupLevel : kMaxGroup;
@@ -864,11 +918,15 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
             }
         }
         // the table of the next layer; the barrier that ends this layer publishes it
-        if (producer && l + 1 < L)
+        if (producer && l + 1 < le)
             publish_entries(table + ((l + 1) & 1) * kMaxFillWaves * kWave, next_fetch, S, lane);
         __syncthreads();
     }
 
+    if constexpr (kBlocks) {
+        if (blocks.pass == 1)
+            return;                              // the final time is known from pass 0
+    }
     // final argmin over t' <= bp within each team
     const float *last = (L & 1) ? buf1 : buf0;
     float bv = __builtin_inff();
@@ -1024,34 +1082,46 @@ __device__ __forceinline__ LayerLevels<kLevelBlocks> load_layer(
     return v;
 }
 
-template <int kLevelBlocks>
+// kBlocks: the walk through one block of layers [blocks.begin, blocks.end) of the small-record
+// solve: rows come from the block record, the row below the block from its checkpoint; tstar
+// holds the time to start from and receives the time below the block; the cost is re-summed
+// after the first block (the last one walked).
+template <int kLevelBlocks, bool kBlocks>
 __global__ __launch_bounds__(kWalkThreads) void dp_backtrace_values(
     const int32_t *__restrict__ tau, ErrSource src, const int32_t *__restrict__ meta,
     const float *__restrict__ drec,
-    const int32_t *__restrict__ tstar, int K, int L, int S, int pitch,
-    int16_t *__restrict__ profile, float *__restrict__ cost, Resume resume)
+    int32_t *__restrict__ tstar, int K, int L, int S, int pitch,
+    int16_t *__restrict__ profile, float *__restrict__ cost, Resume resume, Blocks blocks)
 {
     const int lane = threadIdx.x & (kWave - 1);
     const int k = blockIdx.x * (kWalkThreads / kWave) + threadIdx.x / kWave;
     if (k >= K)
         return;
     int16_t *prof = profile + (size_t)k * L;
+    const int lb = kBlocks ? blocks.begin : 0;   // layers [lb, le) are walked
+    const int le = kBlocks ? blocks.end : L;
     int t = tstar[k];
     if (t < 0) {
-        for (int l = lane; l < L; l += kWave)
-            prof[l] = -1;
+        for (int l = lb + lane; l < le; l += kWave)
+            prof[l] = t == -1 ? -1 : -2;         // -1: no profile meets the budget
         return;
     }
     const float *drec_k = drec + (size_t)k * L * pitch;
     const int l0 = resume.start(k, L);           // rows below l0 are the incumbent's
     auto row_of = [&](int l) {
-        return (l < l0 ? resume.inc_rec : drec_k) + (size_t)l * pitch;
+        if constexpr (kBlocks) {
+            if (l >= lb)
+                return blocks.block + ((size_t)k * blocks.stride + (l - lb)) * pitch;
+            return blocks.ckpt + ((size_t)k * blocks.slots + (lb / blocks.stride - 1)) * pitch;
+        } else {
+            return (l < l0 ? resume.inc_rec : drec_k) + (size_t)l * pitch;
+        }
     };
-    float target = row_of(L - 1)[t];
+    float target = row_of(le - 1)[t];
     LayerLevels<kLevelBlocks> next =
-        load_layer<kLevelBlocks>(tau, src.row(k, L - 1, L, S), meta, L - 1, L, S, lane);
+        load_layer<kLevelBlocks>(tau, src.row(k, le - 1, L, S), meta, le - 1, L, S, lane);
     bool ok = true;
-    for (int l = L - 1; l >= 0; --l) {
+    for (int l = le - 1; l >= lb; --l) {
         const LayerLevels<kLevelBlocks> cur = next;
         const float *prow = row_of(l > 0 ? l - 1 : 0);       // row of layer l - 1
         // issue the gather of D_{l-1} first, then the next layer's table behind it
@@ -1067,7 +1137,7 @@ __global__ __launch_bounds__(kWalkThreads) void dp_backtrace_values(
             if (valid[b])
                 pv[b] = l > 0 ? __builtin_nontemporal_load(&prow[u[b]]) : -0.0f;
         }
-        if (l > 0)
+        if (l > lb)
             next = load_layer<kLevelBlocks>(tau, src.row(k, l - 1, L, S), meta, l - 1, L, S, lane);
         int found = -1, next_t = 0;
         float next_target = 0.0f;
@@ -1096,9 +1166,19 @@ __global__ __launch_bounds__(kWalkThreads) void dp_backtrace_values(
     if (!ok) {
         for (int l = lane; l < L; l += kWave)
             prof[l] = -2;
-        if (lane == 0)
+        if (lane == 0) {
             cost[k] = __builtin_nanf("");
+            if constexpr (kBlocks)
+                tstar[k] = -2;                   // the blocks below are marked the same way
+        }
         return;
+    }
+    if constexpr (kBlocks) {
+        if (lb > 0) {                            // more blocks follow: hand the time down
+            if (lane == 0)
+                tstar[k] = t;
+            return;
+        }
     }
     // lane 0 wrote the profile; make it visible to its own reads, then re-sum in layer order
     __threadfence();
@@ -1115,9 +1195,9 @@ int launch_status()
     return hipGetLastError() == hipSuccess ? SPDY_DP_OK : SPDY_DP_ERR_LAUNCH;
 }
 
-template <bool kLevel, bool kNarrow>
+template <bool kLevel, bool kNarrow, bool kBlocks = false>
 int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume resume, int K, int L,
-                int S, int B, char *ws, float *cost, hipStream_t q)
+                int S, int B, char *ws, float *cost, hipStream_t q, Blocks blocks = Blocks{})
 {
     int32_t *meta = reinterpret_cast<int32_t *>(ws + lay.meta_off);
     int32_t *shifts = reinterpret_cast<int32_t *>(ws + lay.shifts_off);
@@ -1147,8 +1227,8 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     const int lds_large = need <= (size_t)kLdsHalf ? 0
                           : (need <= (size_t)kLdsBytes ? (int)need : kLdsBytes);
     const bool in_memory = need > (size_t)kLdsBytes;      // implies lay.may_spill
-    auto in_lds = dp_fill<kLevel, true, kNarrow>;
-    auto in_global = dp_fill<kLevel, false, kNarrow>;
+    auto in_lds = dp_fill<kLevel, true, kNarrow, kBlocks>;
+    auto in_global = dp_fill<kLevel, false, kNarrow, kBlocks>;
     const int lds_max = lds_large ? lds_large : lds_small;
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(in_lds),
                             hipFuncAttributeMaxDynamicSharedMemorySize, lds_max) != hipSuccess)
@@ -1160,19 +1240,19 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
         hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess ||
         units <= 0)
         return SPDY_DP_ERR_LAUNCH;
-    hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, K, 2 * units, L, S, s8, B,
-                       waves,
-                       max_group, lds_small, lds_large, kLevel ? 0 : 1,
-                       meta, shifts, order, start, entry);
+    if (!(kBlocks && blocks.pass == 1))          // the block passes reuse pass 0's tables
+        hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, K, 2 * units, L, S, s8,
+                           B, waves, max_group, lds_small, lds_large, kLevel ? 0 : 1, meta, shifts,
+                           order, start, entry);
     const LevelTables tables{shifts, order, start, entry, s8};
     hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, tables, 1, K,
-                       L, S, pitch, choice, drec, rows, tstar, cost, resume);
+                       L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     if (lds_large)
         hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, tables,
-                           2, K, L, S, pitch, choice, drec, rows, tstar, cost, resume);
+                           2, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     if (in_memory)
         hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, src, meta, tables, 0, K,
-                           L, S, pitch, choice, drec, rows, tstar, cost, resume);
+                           L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     return launch_status();
 }
 
@@ -1227,10 +1307,12 @@ int backtrace_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B
                            tstar, K, L, S, (int)lay.row, profile, cost);
     } else {
         const int per_block = kWalkThreads / kWave;
-        hipLaunchKernelGGL(S <= kWave ? dp_backtrace_values<1> : dp_backtrace_values<4>,
-                           dim3((K + per_block - 1) / per_block), dim3(kWalkThreads), 0, q, tau,
-                           src, meta, reinterpret_cast<const float *>(ws + lay.record_off), tstar,
-                           K, L, S, (int)lay.row, profile, cost, resume);
+        auto narrow = dp_backtrace_values<1, false>;
+        auto wide = dp_backtrace_values<4, false>;
+        hipLaunchKernelGGL(S <= kWave ? narrow : wide, dim3((K + per_block - 1) / per_block), dim3(kWalkThreads), 0, q, tau,
+                           src, meta, reinterpret_cast<const float *>(ws + lay.record_off),
+                           const_cast<int32_t *>(tstar), K, L, S, (int)lay.row, profile, cost,
+                           resume, Blocks{});
     }
     return launch_status();
 }
@@ -1244,6 +1326,80 @@ int solve_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B, in
     if (st != SPDY_DP_OK)
         return st;
     return backtrace_impl(tau, src, K, L, S, B, profile, cost, workspace, workspace_bytes, stream);
+}
+
+// The stride of the solve with checkpoints: the caller's, or about sqrt(L), which makes the
+// checkpoints and the block record the same size.
+int checkpoint_stride(int L, int stride)
+{
+    if (stride > 0)
+        return stride < L ? stride : L;
+    int j = 1;
+    while ((long long)j * j < L)
+        ++j;
+    return j;
+}
+
+// Pass 0 over all layers (checkpoints, final time), then per block of `stride` layers, last
+// first: fill the block's rows from the checkpoint below it and walk through them.
+int checkpointed_impl(const int32_t *tau, ErrSource src, int K, int L, int S, int B, int stride,
+                      int16_t *profile, float *cost, void *workspace, size_t workspace_bytes,
+                      void *stream)
+{
+    if (!tau || !profile || !cost)
+        return SPDY_DP_ERR_NULL;
+    if (L <= 0)
+        return SPDY_DP_ERR_DIM;
+    const int j = checkpoint_stride(L, stride);
+    const int nblocks = (L + j - 1) / j;
+    const int slots = nblocks - 1;
+    const Layout lay = make_layout(K, L, S, B, workspace_bytes, (long long)slots + j);
+    int st = validate(lay, workspace);
+    if (st != SPDY_DP_OK)
+        return st;
+    if (lay.variant != kValueRecord)
+        return SPDY_DP_ERR_WORKSPACE;
+    hipStream_t q = static_cast<hipStream_t>(stream);
+    char *ws = static_cast<char *>(workspace);
+    (void)hipGetLastError();
+    Blocks blocks{};
+    blocks.stride = j;
+    blocks.slots = slots;
+    blocks.ckpt = reinterpret_cast<float *>(ws + lay.record_off);
+    blocks.block = blocks.ckpt + (size_t)K * slots * lay.row;
+    auto fill = [&]() {
+        return S <= kWave
+                   ? launch_fill<false, true, true>(lay, tau, src, Resume{}, K, L, S, B, ws, cost,
+                                                    q, blocks)
+                   : launch_fill<false, false, true>(lay, tau, src, Resume{}, K, L, S, B, ws, cost,
+                                                     q, blocks);
+    };
+    blocks.pass = 0;
+    blocks.begin = 0;
+    blocks.end = L;
+    st = fill();
+    if (st != SPDY_DP_OK)
+        return st;
+    const int32_t *meta = reinterpret_cast<const int32_t *>(ws + lay.meta_off);
+    int32_t *tstar = reinterpret_cast<int32_t *>(ws + lay.tstar_off);
+    const int per_block = kWalkThreads / kWave;
+    blocks.pass = 1;
+    for (int b = nblocks - 1; b >= 0; --b) {
+        blocks.begin = b * j;
+        blocks.end = (b + 1) * j < L ? (b + 1) * j : L;
+        st = fill();
+        if (st != SPDY_DP_OK)
+            return st;
+        auto narrow = dp_backtrace_values<1, true>;
+        auto wide = dp_backtrace_values<4, true>;
+        hipLaunchKernelGGL(S <= kWave ? narrow : wide, dim3((K + per_block - 1) / per_block), dim3(kWalkThreads), 0, q, tau,
+                           src, meta, nullptr, tstar, K, L, S, (int)lay.row, profile, cost,
+                           Resume{}, blocks);
+        st = launch_status();
+        if (st != SPDY_DP_OK)
+            return st;
+    }
+    return SPDY_DP_OK;
 }
 
 int budgets_impl(const int32_t *tau, ErrSource src, int K, int L, int S, const int32_t *budgets,
@@ -1408,6 +1564,25 @@ int spdy_dp_solve_from_incumbent(const int32_t *tau, const float *err, const int
     return resume_impl(tau, ErrSource{err, nullptr, nullptr}, first_layer, K, L, S, B,
                        incumbent_workspace, incumbent_bytes, profile, cost, workspace,
                        workspace_bytes, stream);
+}
+
+size_t spdy_dp_workspace_bytes_checkpointed(int K, int L, int S, int B, int stride)
+{
+    if (L <= 0)
+        return 0;
+    const int j = checkpoint_stride(L, stride);
+    const Layout lay = make_layout(K, L, S, B, SIZE_MAX, (long long)((L + j - 1) / j - 1) + j);
+    return lay.status == SPDY_DP_OK ? lay.total_value : 0;
+}
+
+int spdy_dp_solve_checkpointed(const int32_t *tau, const float *err, int K, int L, int S, int B,
+                               int stride, int16_t *profile, float *cost, void *workspace,
+                               size_t workspace_bytes, void *stream)
+{
+    if (!err)
+        return SPDY_DP_ERR_NULL;
+    return checkpointed_impl(tau, ErrSource{err, nullptr, nullptr}, K, L, S, B, stride, profile,
+                             cost, workspace, workspace_bytes, stream);
 }
 
 const char *spdy_dp_strerror(int status)

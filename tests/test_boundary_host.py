@@ -75,6 +75,18 @@ def test_workspace_size(binding):
     row = (B + 1 + 63) // 64 * 64
     assert binding.spdy_dp_workspace_bytes_min(K, L, S, B) >= K * L * row + 2 * K * row * 4
     assert binding.spdy_dp_workspace_bytes(K, L, S, B) >= 4 * K * L * row + 2 * K * row * 4
+    # the record with checkpoints: L / stride - 1 checkpoint rows + stride block rows per candidate
+    K, L, S, B = 256, 200, 64, 65536
+    row = (B + 1 + 63) // 64 * 64
+    full = binding.spdy_dp_workspace_bytes(K, L, S, B)
+    auto = binding.spdy_dp_workspace_bytes_checkpointed(K, L, S, B, 0)      # stride 15
+    spill = 2 * K * (row + 1664) * 4            # two rows per candidate in memory (long rows)
+    assert 4 * K * (13 + 15) * row + spill <= auto <= 4 * K * (13 + 15) * row + spill + (1 << 20)
+    assert auto * 5 < full
+    assert binding.spdy_dp_workspace_bytes_checkpointed(K, L, S, B, 10) == \
+        binding.spdy_dp_workspace_bytes_checkpointed(K, L, S, B, 20)        # 19 + 10 = 9 + 20
+    assert binding.spdy_dp_workspace_bytes_checkpointed(K, L, S, B, 1000) >= full   # one block
+    assert binding.spdy_dp_workspace_bytes_checkpointed(K, 0, S, B, 0) == 0
     # invalid sizes -> 0
     for f in (binding.spdy_dp_workspace_bytes, binding.spdy_dp_workspace_bytes_min):
         assert f(0, 1, 1, 1) == 0
@@ -135,6 +147,19 @@ def test_argument_errors_are_reported_before_any_launch(binding):
     small = binding.lib().spdy_dp_workspace_bytes_min(4, 8, 8, 1000)
     assert small < binding.lib().spdy_dp_workspace_bytes(4, 8, 8, 1000)
     assert inc(fake, fake, fake, 4, 8, 8, 1000, far, big, fake, fake, fake, small, None) == \
+        binding.ERR_WORKSPACE
+    ck = lib.spdy_dp_solve_checkpointed
+    assert ck(fake, None, 1, 1, 1, 1, 0, fake, fake, fake, big, None) == binding.ERR_NULL
+    assert ck(None, fake, 1, 1, 1, 1, 0, fake, fake, fake, big, None) == binding.ERR_NULL
+    assert ck(fake, fake, 1, 1, 1, 1, 0, None, fake, fake, big, None) == binding.ERR_NULL
+    assert ck(fake, fake, 1, 0, 1, 1, 0, fake, fake, fake, big, None) == binding.ERR_DIM
+    assert ck(fake, fake, 1, 1, 300, 1, 0, fake, fake, fake, big, None) == binding.ERR_LEVELS
+    assert ck(fake, fake, 1, 1, 1, 1, 0, fake, fake, fake, 8, None) == binding.ERR_WORKSPACE
+    # the workspace of one stride does not serve a stride that needs more rows
+    need4 = binding.spdy_dp_workspace_bytes_checkpointed(8, 64, 8, 4000, 4)
+    need8 = binding.spdy_dp_workspace_bytes_checkpointed(8, 64, 8, 4000, 8)
+    assert need8 < need4 < binding.spdy_dp_workspace_bytes(8, 64, 8, 4000)
+    assert ck(fake, fake, 8, 64, 8, 4000, 4, fake, fake, fake, need8, None) == \
         binding.ERR_WORKSPACE
     assert lib.spdy_dp_fill(fake, fake, 1, 1, 1, 1, None, fake, 1 << 20, None) == binding.ERR_NULL
     bt = lib.spdy_dp_backtrace

@@ -372,6 +372,59 @@ def test_resume_from_an_infeasible_incumbent(dp):
         assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, f"B={B}")
 
 
+CHECKPOINT_SHAPES = [
+    # K, L, S, B, strides: teams in LDS, long rows in LDS, rows in global memory, S > 64, L = 1
+    (37, 9, 8, 2000, (0, 1, 2, 4, 9, 50)),
+    (5, 12, 40, 30000, (0, 5)),
+    (3, 5, 12, 70000, (2,)),
+    (7, 10, 130, 5000, (0, 3)),
+    (4, 1, 6, 100, (0, 3)),
+    (1300, 6, 5, 300, (0, 4)),
+]
+
+
+@pytest.mark.parametrize("shape", CHECKPOINT_SHAPES, ids=lambda s: "K%d_L%d_S%d_B%d" % s[:4])
+def test_checkpointed_solve_bit_exact(dp, shape):
+    K, L, S, B, strides = shape
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(K + 31 * L + 977 * S)
+    for variant in range(3):
+        kw = dict(tau_max=max(1, B // max(1, L // 2)))
+        if variant == 1:
+            kw.update(integer_err=3, zero_tau_frac=0.2)
+        elif variant == 2:
+            kw.update(over_budget_frac=0.3, inf_err_frac=0.1, layer_floor=B // L)
+        tau, err, _ = workloads.random_instance(rng, K, L, S, B, **kw)
+        if variant == 2:
+            err[0, 0, :] = np.inf                 # candidate 0 has no feasible profile
+        p_ref, c_ref = oracle.solve_ref(tau, err, B, threads=CPU_THREADS)
+        for stride in strides:
+            print(f"[parity] checkpointed K={K} L={L} S={S} B={B} stride={stride} v{variant}",
+                  flush=True)
+            n = dp.spdy_dp_workspace_bytes_checkpointed(K, L, S, B, stride)
+            ws = torch.empty(n, dtype=torch.uint8, device=dev)
+            ws.fill_(0xC3)
+            profile = torch.full((K, L), -7, dtype=torch.int16, device=dev)
+            cost = torch.full((K,), -7.0, dtype=torch.float32, device=dev)
+            dp.spdy_dp_solve_checkpointed(torch.from_numpy(tau).to(dev),
+                                          torch.from_numpy(err).to(dev), B, stride, profile, cost,
+                                          ws)
+            torch.cuda.synchronize()
+            assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref,
+                        f"{shape[:4]} stride {stride} variant {variant}")
+
+
+def test_checkpointed_solve_on_a_benchmark_shape(dp, reference):
+    dev = torch.device("cuda:0")
+    cfg = workloads.CONFIGS["rn50_k1024"]
+    tau, err, B = workloads.generate(cfg)
+    p_ref, c_ref = reference("rn50_k1024", tau, err, B)
+    profile, cost = dp.spdy_dp_solve_checkpointed(torch.from_numpy(tau).to(dev),
+                                                  torch.from_numpy(err).to(dev), B)
+    torch.cuda.synchronize()
+    assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, "rn50_k1024 checkpointed")
+
+
 def test_one_workspace_reused_across_different_problems(dp):
     """Nothing a call leaves in the workspace may matter to the next one, whatever its shape."""
     dev = torch.device("cuda:0")
