@@ -25,11 +25,14 @@
  *   - a level with tau > B, or with err = +inf, is never chosen; tau = 0 is legal;
  *   - a candidate that no profile satisfies gets cost = +inf and profile = -1 (status stays OK).
  *
- * Two exact reductions of Alg. 1's table are applied on the device (results are unchanged):
+ * Exact reductions of Alg. 1's table are applied on the device (results are unchanged):
  *   - every layer's smallest time m_l = min_s tau[l][s] is subtracted from that layer's times
  *     and M = sum_l m_l from the budget, so layer l's row only spans t' = t - (m_0 + .. + m_l)
  *     in [0, B - M] (cells outside can never lie on a profile that meets the budget);
- *   - cells beyond the largest time reachable after l layers are +inf and are not computed.
+ *   - cells beyond the largest time reachable after l layers are +inf and are not computed;
+ *   - when D itself is recorded, levels of a layer that take the same time are served by one
+ *     update with the smallest of their errors (they read the same cell of D_{l-1}, and a
+ *     rounded add is monotone in the addend); the walk back still picks the smallest level.
  *
  * What is recorded per cell for the walk back depends on the workspace the caller provides:
  *   - spdy_dp_workspace_bytes():     D itself (fp32 per cell); the fill then needs only an add
@@ -170,8 +173,8 @@ int spdy_dp_solve_checkpointed(const int32_t *tau, const float *err, int K, int 
  *   out[0] variant: 0 = fp32 D record, 1 = one-byte level record
  *   out[1] byte offset of the int32 header: [0] B - M (or -1 if M > B: nobody is feasible),
  *          [1] M, [2] reduced row length (B - M + 1 padded to 64), [3] 0 if the rows live in
- *          global memory (per-layer kernels), 1 or 2 if they live in LDS; then m_l at [8 + l]
- *          and the number of computed 64-bucket chunks of layer l at [8 + L + l]
+ *          global memory, 1 or 2 if they live in LDS; then m_l at [8 + l] and the number of
+ *          computed 64-bucket chunks of layer l at [8 + L + l]
  *   out[2] byte offset of int32 t*[K] (reduced time t* - M, or -1 if infeasible)
  *   out[3] byte offset of the record
  *   out[4] record pitch in elements (buckets per row, a multiple of 64)
