@@ -56,6 +56,32 @@ def executed_updates_per_candidate(tau: np.ndarray, B: int, merge_equal_times: b
                    for l in range(t.shape[0])))
 
 
+def executed_updates_level_record(tau: np.ndarray, err: np.ndarray, B: int) -> int:
+    """The same count for the level record, summed over the candidates: every level is visited
+    except those that cannot win (an earlier level of the layer takes the same time with an error
+    no larger), which depends on the candidate's errors."""
+    t = tau.astype(np.int64)
+    mn = t.min(axis=1)
+    bp = B - int(mn.sum())
+    if bp < 0:
+        return 0
+    delta = t - mn[:, None]
+    span = np.where(delta <= bp, delta, 0).max(axis=1)
+    top = np.minimum(np.cumsum(span), bp)
+    total = 0
+    for l in range(t.shape[0]):
+        for d in np.unique(delta[l]):
+            if d > top[l]:
+                continue
+            idx = np.flatnonzero(delta[l] == d)               # ascending level index
+            e = err[:, l, idx]
+            visit = np.ones(e.shape, dtype=bool)
+            if idx.size > 1:
+                visit[:, 1:] = e[:, 1:] < np.minimum.accumulate(e, axis=1)[:, :-1]
+            total += int(visit.sum()) * int(top[l] + 1 - d)
+    return total
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -213,7 +239,12 @@ def main() -> int:
     fill_ms = float(np.mean([a.elapsed_time(b) for a, b in evs if a is not None]))
 
     nominal = K * L * S * B
-    executed = K * executed_updates_per_candidate(tau, B, args.record == "d")
+    if args.record == "d":
+        executed = K * executed_updates_per_candidate(tau, B, True)
+    elif S <= 64:
+        executed = executed_updates_level_record(tau, err, B)
+    else:                                         # more than 64 levels: every level is visited
+        executed = K * executed_updates_per_candidate(tau, B, False)
     value = nominal / (ms_per_step * 1e-3)
     ops = LANE_OPS_PER_UPDATE[args.record]
     achieved = executed * ops / (fill_ms * 1e-3)

@@ -30,9 +30,11 @@
  *     and M = sum_l m_l from the budget, so layer l's row only spans t' = t - (m_0 + .. + m_l)
  *     in [0, B - M] (cells outside can never lie on a profile that meets the budget);
  *   - cells beyond the largest time reachable after l layers are +inf and are not computed;
- *   - when D itself is recorded, levels of a layer that take the same time are served by one
- *     update with the smallest of their errors (they read the same cell of D_{l-1}, and a
- *     rounded add is monotone in the addend); the walk back still picks the smallest level.
+ *   - levels of a layer that take the same time read the same cell of D_{l-1}, and a rounded
+ *     add is monotone in the addend: when D itself is recorded they are served by one update
+ *     with the smallest of their errors (the walk back still picks the smallest level); when
+ *     the level is recorded, a level is not visited if an earlier one of the same time has an
+ *     error no larger (the strict "<" could never select it).
  *
  * What is recorded per cell for the walk back depends on the workspace the caller provides:
  *   - spdy_dp_workspace_bytes():     D itself (fp32 per cell); the fill then needs only an add

@@ -309,6 +309,7 @@ __device__ void prepare_order(const int32_t *__restrict__ tau, int l, int S, int
     const int s = threadIdx.x;
     int32_t *shifts_l = shifts + (size_t)l * s8;
     int32_t *order_l = order + (size_t)l * s8;
+    bool twin = false;                            // a later level of the layer takes the same time
     if (s < S) {
         const int32_t *tau_l = tau + (size_t)l * S;
         const int mine = tau_l[s];
@@ -317,6 +318,7 @@ __device__ void prepare_order(const int32_t *__restrict__ tau, int l, int S, int
             const int other = tau_l[o];
             m = min(m, other);
             rank += (other < mine || (other == mine && o < s)) ? 1 : 0;
+            twin |= o > s && other == mine;
         }
         if (!sorted)
             rank = s;
@@ -332,10 +334,18 @@ __device__ void prepare_order(const int32_t *__restrict__ tau, int l, int S, int
         if (!sorted)
             shifts_l[s] = INT32_MAX;
     }
-    if (!sorted)
-        return;
-    __syncthreads();
     int32_t *start_l = start + (size_t)l * (s8 + kBatch);
+    if (!sorted) {
+        // level order: start[0..1] holds, for the first 64 levels, the set of those that have
+        // such a twin (the only ones that can make a later level not worth visiting)
+        const unsigned long long twins = __ballot(twin);
+        if (s == 0) {
+            start_l[0] = (int32_t)(twins & 0xFFFFFFFFull);
+            start_l[1] = (int32_t)(twins >> 32);
+        }
+        return;
+    }
+    __syncthreads();
     const int r = threadIdx.x;                    // a position of the sorted order
     if (r < S) {
         int entry = 0;                            // distinct shifts before position r
@@ -461,6 +471,7 @@ struct Blocks {
 struct LevelEntry {   // one visited level of one layer of one candidate
     int32_t shift;    // tau - m_l (INT32_MAX in padding entries)
     float err;
+    unsigned long long keep = ~0ull;   // wave-uniform: which of the first 64 entries to visit
 };
 
 // The prepare kernel's tables of one layer (see prepare_order).
@@ -534,6 +545,32 @@ __device__ __forceinline__ LevelFetch fetch_levels(LayerTable tl, ErrRow er, int
     return f;
 }
 
+// Level record: a level need not be visited when an earlier level of the layer takes the same
+// time with an error no larger: it reads the same cell of D_{l-1}, a rounded add is monotone in
+// the addend, so its value cannot be strictly smaller than the earlier one's and the strict "<"
+// never selects it.  Bit r of the result is set when level r has to be visited; one wave.
+// `twins`: the levels that have a later level of the same time (from the prepare kernel).
+__device__ __forceinline__ unsigned long long levels_to_visit(const LevelFetch &f,
+                                                              unsigned long long twins, int lane)
+{
+    bool skip = false;
+    while (twins) {
+        const int r = __builtin_ctzll(twins);
+        twins &= twins - 1;
+        const int shift = __builtin_amdgcn_readlane(f.shift, r);
+        const float err = __builtin_bit_cast(
+            float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, f.raw), r));
+        skip |= lane > r && f.shift == shift && err <= f.raw;
+    }
+    return __ballot(!skip);
+}
+
+__device__ __forceinline__ unsigned long long load_twins(LayerTable tl)
+{
+    return (unsigned long long)(uint32_t)tl.start[0] |
+           ((unsigned long long)(uint32_t)tl.start[1] << 32);
+}
+
 // table[r] = smallest error among the levels of entry r (+inf for unused entries); one wave.
 __device__ __forceinline__ void publish_entries(float *table, const LevelFetch &f, int S, int lane)
 {
@@ -590,6 +627,8 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, Leve
         const LevelEntry mine =
             blk == 0 ? first : load_level<kLevel>(tl, er, s8, blk, lane);
         unsigned long long use = __ballot(mine.shift <= last);
+        if (blk == 0)
+            use &= first.keep;
         if constexpr (kLevel) {
             while (use) {
                 const int i = __builtin_ctzll(use);
@@ -754,7 +793,9 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     extern __shared__ float lds[];
     __shared__ float s_best[kMaxFillWaves];
     __shared__ int s_time[kMaxFillWaves];
-    __shared__ float s_entries[2][kMaxFillWaves][kWave];   // per team: merged errors, two layers
+    // per team and for two layers: merged errors (D record), or in the same storage one 64-bit
+    // set of levels to visit (level record)
+    __shared__ __attribute__((aligned(8))) float s_entries[2][kMaxFillWaves][kWave];
     if (meta[kMetaPath] != path)
         return;                                  // another launch does the work
     const int bp = meta[kMetaBudget];
@@ -843,18 +884,29 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
 
     // lane i keeps visited entry i of the layer being swept; the next layer's is fetched early
     const int s8 = tables.s8;
-    constexpr bool kShared = kNarrow && !kLevel;  // merged errors go through the team's table
-    const bool producer = kShared && wv == 0 && team < teams;
+    // S <= 64: the first wave of a team prepares, for the next layer, the team's table of merged
+    // errors (D record) or the set of levels worth visiting (level record)
+    constexpr bool kShared = kNarrow && !kLevel;
+    const bool producer = kNarrow && wv == 0 && team < teams;
+    unsigned long long *keep =
+        reinterpret_cast<unsigned long long *>(&s_entries[0][0][0]) + (team < teams ? team : 0);
     float *table = &s_entries[0][team < teams ? team : 0][0];
     LevelEntry next_first{INT32_MAX, 0.0f};
     LevelFetch next_fetch{INT32_MAX, 0.0f, 0};
     if constexpr (kNarrow) {
         next_fetch = fetch_levels<kLevel>(tables.layer(lb), mine.layer(lb, S), S, s8, lane,
                                           producer);
-        if (producer)
-            publish_entries(table + (lb & 1) * kMaxFillWaves * kWave, next_fetch, S, lane);
-        if constexpr (kShared)
-            __syncthreads();
+        if (producer) {
+            if constexpr (kLevel) {
+                const unsigned long long visit =
+                    levels_to_visit(next_fetch, load_twins(tables.layer(lb)), lane);
+                if (lane == 0)
+                    keep[(lb & 1) * kMaxFillWaves] = visit;
+            } else {
+                publish_entries(table + (lb & 1) * kMaxFillWaves * kWave, next_fetch, S, lane);
+            }
+        }
+        __syncthreads();
     } else {
         next_first = load_level<kLevel>(tables.layer(lb), mine.layer(lb, S), s8, 0, lane);
     }
@@ -867,6 +919,8 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
         if constexpr (kNarrow) {
             first.shift = next_fetch.shift;
             first.err = kLevel ? next_fetch.raw : table[(l & 1) * kMaxFillWaves * kWave + lane];
+            if constexpr (kLevel)
+                first.keep = keep[(l & 1) * kMaxFillWaves];
         }
         if (l + 1 < le) {
             const LayerTable tn = tables.layer(l + 1);
@@ -918,8 +972,17 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
             }
         }
         // the table of the next layer; the barrier that ends this layer publishes it
-        if (producer && l + 1 < le)
-            publish_entries(table + ((l + 1) & 1) * kMaxFillWaves * kWave, next_fetch, S, lane);
+        if (producer && l + 1 < le) {
+            if constexpr (kLevel) {
+                const unsigned long long visit =
+                    levels_to_visit(next_fetch, load_twins(tables.layer(l + 1)), lane);
+                if (lane == 0)
+                    keep[((l + 1) & 1) * kMaxFillWaves] = visit;
+            } else {
+                publish_entries(table + ((l + 1) & 1) * kMaxFillWaves * kWave, next_fetch, S,
+                                lane);
+            }
+        }
         __syncthreads();
     }
 
