@@ -521,3 +521,40 @@ def test_reduced_table_equals_alg1_on_the_cells_that_matter():
         assert F32(prev[t_red]) == F32(cost) or (np.isinf(cost) and np.isinf(prev[t_red]))
         if np.isfinite(cost):
             assert t_red + int(m.sum()) == int(np.argmin(D[L - 1]))
+
+
+def test_levels_that_cannot_win_may_be_left_out():
+    """Alg. 1 with the levels in index order and strict "<", but leaving out every level for
+    which an earlier level of the layer takes the same time with an error no larger: D and P must
+    equal the oracle's everywhere D is finite (what the level-recording device sweep does)."""
+    rng = np.random.default_rng(41)
+    skipped = 0
+    for case in range(30):
+        L, S, B = int(rng.integers(1, 6)), int(rng.integers(2, 10)), int(rng.integers(5, 80))
+        tau = rng.integers(0, 7, size=(L, S)).astype(np.int32)      # many equal times
+        if case % 2:
+            err = rng.integers(0, 3, size=(1, L, S)).astype(F32)     # equal errors too
+        else:
+            err = rng.random((1, L, S)).astype(F32)
+        D_ref, P_ref, _, _ = oracle.tables_ref(tau, err, B)
+        prev = np.full(B + 1, np.inf, dtype=F32)
+        prev[0] = F32(-0.0)
+        for l in range(L):
+            cur = np.full(B + 1, np.inf, dtype=F32)
+            arg = np.full(B + 1, -1, dtype=np.int64)
+            for s in range(S):
+                d = int(tau[l, s])
+                if d > B:
+                    continue
+                if any(tau[l, q] == d and err[0, l, q] <= err[0, l, s] for q in range(s)):
+                    skipped += 1
+                    continue
+                cand = (prev[:B + 1 - d] + err[0, l, s]).astype(F32)
+                better = cand < cur[d:]
+                cur[d:][better] = cand[better]
+                arg[d:][better] = s
+            fin = np.isfinite(D_ref[l])
+            assert np.array_equal(cur, D_ref[l]), f"case {case} layer {l}"
+            assert np.array_equal(arg[fin], P_ref[l][fin]), f"case {case} layer {l}"
+            prev = cur
+    assert skipped > 50
