@@ -425,6 +425,45 @@ def test_checkpointed_solve_on_a_benchmark_shape(dp, reference):
     assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, "rn50_k1024 checkpointed")
 
 
+def test_many_random_shapes_through_every_entry_point(dp):
+    """Seeded sweep over small random shapes: the plain solve with both records, the solve with
+    checkpoints, several budgets and the sensitivity form, all against the oracle."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(2024)
+    for case in range(40):
+        K = int(rng.integers(1, 9))
+        L = int(rng.integers(1, 12))
+        S = int(rng.choice([1, 2, 3, 5, 8, 17, 40, 64, 65, 100]))
+        B = int(rng.choice([0, 1, 7, 63, 64, 200, 1000, 5000]))
+        kw = dict(tau_max=max(1, B // max(1, L // 2)), zero_tau_frac=float(rng.choice([0, 0.2])),
+                  over_budget_frac=float(rng.choice([0, 0.1])),
+                  integer_err=int(rng.choice([0, 2, 4])) or None)
+        tau, err, _ = workloads.random_instance(rng, K, L, S, B, **kw)
+        print(f"[parity] sweep {case}: K={K} L={L} S={S} B={B}", flush=True)
+        p_ref, c_ref = oracle.solve_ref(tau, err, B)
+        tau_d, err_d = torch.from_numpy(tau).to(dev), torch.from_numpy(err).to(dev)
+        for compact in (False, True):
+            p, c, _ = gpu_solve(dp, tau, err, B, compact=compact)
+            assert_same(p, c, p_ref, c_ref, f"sweep {case} compact={compact}")
+        p, c = dp.spdy_dp_solve_checkpointed(tau_d, err_d, B, int(rng.integers(0, 5)))
+        torch.cuda.synchronize()
+        assert_same(p.cpu().numpy(), c.cpu().numpy(), p_ref, c_ref, f"sweep {case} checkpointed")
+        budgets = [B, B // 2, max(0, B - 1)]
+        p, c = dp.spdy_dp_solve_budgets(tau_d, err_d, budgets)
+        torch.cuda.synchronize()
+        pb, cb = oracle.solve_budgets_ref(tau, err, budgets)
+        for j in range(len(budgets)):
+            assert_same(p[j].cpu().numpy(), c[j].cpu().numpy(), pb[j], cb[j],
+                        f"sweep {case} budget {budgets[j]}")
+        cs = rng.random((K, L)).astype(np.float32)
+        w = np.sort(rng.random(S)).astype(np.float32)
+        p, c = dp.spdy_dp_solve_sensitivities(tau_d, torch.from_numpy(cs).to(dev),
+                                              torch.from_numpy(w).to(dev), B)
+        torch.cuda.synchronize()
+        ps, cs_ref = oracle.solve_sens_ref(tau, cs, w, B)
+        assert_same(p.cpu().numpy(), c.cpu().numpy(), ps, cs_ref, f"sweep {case} sensitivities")
+
+
 def test_one_workspace_reused_across_different_problems(dp):
     """Nothing a call leaves in the workspace may matter to the next one, whatever its shape."""
     dev = torch.device("cuda:0")
