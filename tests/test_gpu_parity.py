@@ -1,7 +1,5 @@
 """GPU parity: the HIP path against the CPU oracle, bit for bit (profiles, fp32 costs, and the
 per-cell level record wherever the oracle's D is finite), through the C-ABI binding."""
-import os
-
 import numpy as np
 import pytest
 
