@@ -1292,9 +1292,9 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     const bool in_memory = need > (size_t)kLdsBytes;      // implies lay.may_spill
     auto in_lds = dp_fill<kLevel, true, kNarrow, kBlocks>;
     auto in_global = dp_fill<kLevel, false, kNarrow, kBlocks>;
-    const int lds_max = lds_large ? lds_large : lds_small;
+    // always the same limit, so that calls from several host threads cannot undo each other's
     if (hipFuncSetAttribute(reinterpret_cast<const void *>(in_lds),
-                            hipFuncAttributeMaxDynamicSharedMemorySize, lds_max) != hipSuccess)
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
         return SPDY_DP_ERR_LAUNCH;
 
     // workgroups the chip holds at once: two per compute unit for either variant
