@@ -462,6 +462,43 @@ def test_many_random_shapes_through_every_entry_point(dp):
         assert_same(p.cpu().numpy(), c.cpu().numpy(), ps, cs_ref, f"sweep {case} sensitivities")
 
 
+def test_two_host_threads_on_their_own_streams(dp):
+    """The library keeps no state between calls: two host threads, each with its own stream,
+    workspace and problem shape, solve concurrently."""
+    import threading
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(314)
+    problems = []
+    for (K, L, S, B) in [(9, 10, 12, 3000), (5, 7, 70, 30000)]:   # small and large LDS limits
+        tau, err, _ = workloads.random_instance(rng, K, L, S, B, tau_max=B // 3, integer_err=4)
+        problems.append((tau, err, B, oracle.solve_ref(tau, err, B)))
+    failures = []
+
+    def work(i):
+        try:
+            torch.cuda.set_device(dev)
+            tau, err, B, (p_ref, c_ref) = problems[i]
+            stream = torch.cuda.Stream()
+            tau_d, err_d = torch.from_numpy(tau).to(dev), torch.from_numpy(err).to(dev)
+            K, L, S = err.shape
+            ws = dp.alloc_workspace(K, L, S, B, dev)
+            torch.cuda.synchronize()
+            for _ in range(15):
+                profile, cost = dp.spdy_dp_solve_batched(tau_d, err_d, B, workspace=ws,
+                                                         stream=stream)
+                stream.synchronize()
+                assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, f"thread {i}")
+        except Exception as e:                      # report from the main thread
+            failures.append(repr(e))
+
+    threads = [threading.Thread(target=work, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not failures, failures
+
+
 def test_one_workspace_reused_across_different_problems(dp):
     """Nothing a call leaves in the workspace may matter to the next one, whatever its shape."""
     dev = torch.device("cuda:0")
