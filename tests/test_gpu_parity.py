@@ -462,6 +462,42 @@ def test_many_random_shapes_through_every_entry_point(dp):
         assert_same(p.cpu().numpy(), c.cpu().numpy(), ps, cs_ref, f"sweep {case} sensitivities")
 
 
+def test_a_solve_captured_in_a_graph_replays_correctly(dp):
+    """The library neither allocates nor synchronises, so a solve can be captured into a HIP
+    graph; every replay, with eager work and synchronisations in between, must equal the oracle."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(606)
+    K, L, S, B = 6, 9, 12, 2000
+    tau, err, _ = workloads.random_instance(rng, K, L, S, B, tau_max=B // 4, integer_err=3)
+    other = workloads.random_instance(rng, K, L, S, B, tau_max=B // 4)[1]
+    p_ref, c_ref = oracle.solve_ref(tau, err, B)
+    p_other, c_other = oracle.solve_ref(tau, other, B)
+    tau_d = torch.from_numpy(tau).to(dev)
+    err_d = torch.from_numpy(err).to(dev)        # the graph reads whatever this buffer holds
+    ws = dp.alloc_workspace(K, L, S, B, dev)
+    profile = torch.empty((K, L), dtype=torch.int16, device=dev)
+    cost = torch.empty((K,), dtype=torch.float32, device=dev)
+    dp.spdy_dp_solve_batched(tau_d, err_d, B, profile, cost, ws)     # warm up outside the capture
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            dp.spdy_dp_solve_batched(tau_d, err_d, B, profile, cost, ws)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        table, want = (err, (p_ref, c_ref)) if rep % 2 == 0 else (other, (p_other, c_other))
+        err_d.copy_(torch.from_numpy(table).to(dev))
+        profile.fill_(-9)
+        cost.fill_(-9.0)
+        eager_p, eager_c = dp.spdy_dp_solve_batched(tau_d, err_d, B)  # eager work in between
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_same(profile.cpu().numpy(), cost.cpu().numpy(), *want, f"replay {rep}")
+        assert_same(eager_p.cpu().numpy(), eager_c.cpu().numpy(), *want, f"eager {rep}")
+
+
 def test_two_host_threads_on_their_own_streams(dp):
     """The library keeps no state between calls: two host threads, each with its own stream,
     workspace and problem shape, solve concurrently."""
