@@ -99,7 +99,7 @@ float time_ms(F launch, int reps)
     hipEvent_t a, b;
     CHECK(hipEventCreate(&a));
     CHECK(hipEventCreate(&b));
-    for (int i = 0; i < 3; ++i)
+    for (int i = 0; i < 200; ++i)     // some tens of milliseconds: the core clock settles
         launch();
     CHECK(hipDeviceSynchronize());
     CHECK(hipEventRecord(a));
@@ -135,8 +135,8 @@ int main()
     printf("VALU add+cmp+2 sel  : %.3f ms  %.2f Tlane-op/s  %.1f lane-ops/clk/CU\n", ms,
            ops / ms / 1e9, ops / (ms * 1e-3) / clk / cus);
 
-    const int words = 16384;   // 64 KB per workgroup, two workgroups per CU
-    const int nb = cus * 2;
+    const int words = 8192;    // 32 KB per workgroup, four workgroups (16 waves) per CU
+    const int nb = cus * 4;
     CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(lds_read<int>),
                               hipFuncAttributeMaxDynamicSharedMemorySize, words * 4));
     CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(lds_read<int2>),
