@@ -52,6 +52,15 @@ constexpr int kLdsStatic = 8192 + 256;    // the fill kernel's static LDS (entry
 constexpr int kLdsBytes = 160 * 1024 - kLdsStatic;       // dynamic LDS a workgroup can get
 constexpr int kLdsHalf = 80 * 1024 - kLdsStatic;         // lets two workgroups share a compute unit
 constexpr int kHalo = kMaxGroup * kWave;  // +inf apron left of every row (one group width)
+// The longest row the waves of a workgroup can hold in registers (and so update in place), with
+// its apron, fits the smaller LDS allocation for either record, and two rows that are any longer
+// do not: the in-place case and the launch with the smaller allocation coincide.
+constexpr bool kInPlaceFits =
+    (kFillWaves * kMaxGroup * kWave + kHalo) * 4 <= kLdsHalf &&
+    (kFillWavesLevel * kMaxGroupLevel * kWave + kHalo) * 4 <= kLdsHalf &&
+    2 * (kFillWaves * kMaxGroup * kWave + kWave + kHalo) * 4 > kLdsHalf &&
+    2 * (kFillWavesLevel * kMaxGroupLevel * kWave + kWave + kHalo) * 4 > kLdsHalf;
+static_assert(kInPlaceFits, "path 1 must be exactly the in-place case");
 constexpr int kBatch = 8;                 // level tables are padded to a multiple of this
 constexpr unsigned kNoLevel = 0xFF;
 constexpr size_t kAlign = 256;
@@ -224,12 +233,12 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots
             const long long one_row = ((long long)rowp + kHalo) * (long long)sizeof(float);
             const int want = (rowp / kWave + max_group - 1) / max_group;   // waves per candidate
             inplace = want <= waves ? 1 : 0;
+            // a row updated in place always fits lds_small (kInPlaceFits), so path 1 is exactly
+            // the in-place case
             const long long team_lds = inplace ? one_row : 2 * one_row;
-            const int lds = team_lds <= lds_small ? lds_small : lds_large;
-            path = team_lds <= lds_small ? 1 : (team_lds <= lds_large ? 2 : 0);
-            if (path == 0)
-                inplace = 0;                      // rows in global memory always alternate
-            if (path != 0 && inplace) {
+            const int lds = lds_small;
+            path = inplace ? 1 : (team_lds <= lds_large ? 2 : 0);
+            if (inplace) {
                 // as many candidates per workgroup as keeps every wave at <= max_group chunks
                 teams = waves / want;
                 const long long fit = lds / team_lds;
@@ -623,6 +632,7 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, Leve
         return reinterpret_cast<const float *>(pl - (size_t)((unsigned)shift * 4u));
     };
 
+    // (with S <= 64 this loop runs once; telling the compiler so made the code slower)
     for (int blk = 0; blk < s8; blk += kWave) {
         const LevelEntry mine =
             blk == 0 ? first : load_level<kLevel>(tl, er, s8, blk, lane);
@@ -773,22 +783,24 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 // The fill (Eq. 2-3 for all L layers) and the final argmin over t.  The waves of a workgroup
 // form `teams` teams of `tw` waves; team i of workgroup b solves candidate b * teams + i.
 // Barriers are workgroup-wide, so every team steps through the layers together.
-//   kLds     : the rows live in LDS (`path` 1 or 2); otherwise in `rows` in global memory
-//              (`path` 0: one candidate per workgroup, two rows of kHalo + pitch floats each)
-//   in place : a layer is swept, barrier, written back to the same row, barrier; otherwise two
-//              rows alternate with one barrier per layer
+//   kPath    : which of the launches this is (it returns at once unless the prepare kernel chose
+//              it).  1: rows in LDS, updated in place: a layer is swept, barrier, written back to
+//              the same row, barrier.  2: two rows in LDS alternate, one barrier per layer.
+//              0: two rows of kHalo + pitch floats in `rows` in global memory, one candidate per
+//              workgroup.  (A row that can be updated in place always fits the smaller LDS
+//              allocation and two longer ones never do, so path 1 is exactly the in-place case;
+//              each instantiation holds only its own way of stepping through a layer.)
 //   kNarrow  : S <= 64, one lane per level: the next layer's table is loaded without dependent
 //              loads while a layer is swept (a separate instantiation, so that the waits of the
 //              two ways of loading do not meet in one control-flow join)
 //   kBlocks  : the checkpoint / block passes of the small-record solve (D record only); the
 //              plain instantiation ignores `blocks`
 // `pitch` is the record's row pitch (elements per (k, l) row).
-template <bool kLevel, bool kLds, bool kNarrow, bool kBlocks>
+template <bool kLevel, int kPath, bool kNarrow, bool kBlocks>
 __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void dp_fill(
-    ErrSource src, const int32_t *__restrict__ meta, LevelTables tables, int path, int K, int L,
-    int S, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
-    float *__restrict__ rows, int32_t *__restrict__ tstar, float *__restrict__ cost, Resume resume,
-    Blocks blocks)
+    ErrSource src, const int32_t *__restrict__ meta, LevelTables tables, int K, int L, int S,
+    int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec, float *__restrict__ rows,
+    int32_t *__restrict__ tstar, float *__restrict__ cost, Resume resume, Blocks blocks)
 {
     extern __shared__ float lds[];
     __shared__ float s_best[kMaxFillWaves];
@@ -796,7 +808,8 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     // per team and for two layers: merged errors (D record), or in the same storage one 64-bit
     // set of levels to visit (level record)
     __shared__ __attribute__((aligned(8))) float s_entries[2][kMaxFillWaves][kWave];
-    if (meta[kMetaPath] != path)
+    constexpr bool kLds = kPath != 0, inplace = kPath == 1;
+    if (meta[kMetaPath] != kPath)
         return;                                  // another launch does the work
     const int bp = meta[kMetaBudget];
     const int tid = threadIdx.x, nthreads = blockDim.x;
@@ -807,7 +820,6 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     }
     const int teams = meta[kMetaTeams];
     const int tw = meta[kMetaTeamWaves];
-    const bool inplace = meta[kMetaInPlace] != 0;
     if ((long long)blockIdx.x * teams >= K)
         return;                                  // the first ceil(K / teams) workgroups suffice
     const int row = meta[kMetaRow];
@@ -886,7 +898,6 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     const int s8 = tables.s8;
     // S <= 64: the first wave of a team prepares, for the next layer, the team's table of merged
     // errors (D record) or the set of levels worth visiting (level record)
-    constexpr bool kShared = kNarrow && !kLevel;
     const bool producer = kNarrow && wv == 0 && team < teams;
     unsigned long long *keep =
         reinterpret_cast<unsigned long long *>(&s_entries[0][0][0]) + (team < teams ? team : 0);
@@ -958,7 +969,7 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
         const ErrRow er = mine.layer(l, S);
         constexpr int kMax = kLevel ? kMaxGroupLevel : kMaxGroup;
         const Pending pending{&next_fetch, &next_first};
-        if (inplace) {                           // c_end - c <= kMax by construction
+        if constexpr (inplace) {                 // c_end - c <= kMax by construction
             fill_group_n<kLevel, true>(min(c_end - c, kMax), prev, cur, choice_l, drec_l, first,
                                        tl, er, s8, c * kWave, lane, pending);
         } else {
@@ -1290,10 +1301,12 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     const int lds_large = need <= (size_t)kLdsHalf ? 0
                           : (need <= (size_t)kLdsBytes ? (int)need : kLdsBytes);
     const bool in_memory = need > (size_t)kLdsBytes;      // implies lay.may_spill
-    auto in_lds = dp_fill<kLevel, true, kNarrow, kBlocks>;
-    auto in_global = dp_fill<kLevel, false, kNarrow, kBlocks>;
+    auto in_place = dp_fill<kLevel, 1, kNarrow, kBlocks>;
+    auto two_rows = dp_fill<kLevel, 2, kNarrow, kBlocks>;
+    auto in_global = dp_fill<kLevel, 0, kNarrow, kBlocks>;
     // always the same limit, so that calls from several host threads cannot undo each other's
-    if (hipFuncSetAttribute(reinterpret_cast<const void *>(in_lds),
+    if (lds_large &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(two_rows),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
         return SPDY_DP_ERR_LAUNCH;
 
@@ -1308,14 +1321,14 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
                            B, waves, max_group, lds_small, lds_large, kLevel ? 0 : 1, meta, shifts,
                            order, start, entry);
     const LevelTables tables{shifts, order, start, entry, s8};
-    hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, tables, 1, K,
+    hipLaunchKernelGGL(in_place, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, tables, K,
                        L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     if (lds_large)
-        hipLaunchKernelGGL(in_lds, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, tables,
-                           2, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
+        hipLaunchKernelGGL(two_rows, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, tables,
+                           K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     if (in_memory)
-        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, src, meta, tables, 0, K,
-                           L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
+        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, src, meta, tables, K, L,
+                           S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     return launch_status();
 }
 
