@@ -83,6 +83,12 @@ def check_tables(dp, tau, err_k, B, ws, k, K):
     rec = rec.view(np.float32 if esize == 4 else np.uint8).reshape(rows, pitch)
     if meta[3] == 0:     # rows in global memory: the reduced rows (plus aprons) exceed LDS
         assert 2 * (meta[2] + 1664) * 4 > 160 * 1024 - 8448   # apron 26 * 64, static LDS 8448
+    # the launch with the small LDS allocation is exactly the one that updates a row in place:
+    # the row fits the registers of a workgroup's waves (8 x 26 chunks, or 16 x 10 with levels)
+    fits = meta[2] // 64 <= (8 * 26 if lay["variant"] == 0 else 16 * 10)
+    assert (meta[3] == 1) == bool(meta[6]) == bool(fits)
+    if meta[3] == 2:
+        assert 2 * (meta[2] + 1664) * 4 <= 160 * 1024 - 8448
     for l in range(L):
         n = int(min(nact[l] * 64, bp + 1))
         want_D = D[l, lo[l]:lo[l] + n]
