@@ -47,6 +47,7 @@ constexpr int kFillWaves = 8;        // waves of a fill workgroup (D record)
 constexpr int kFillWavesLevel = 16;  // (level record)
 constexpr int kMaxFillWaves = 16;
 template <bool kLevel> constexpr int fill_waves() { return kLevel ? kFillWavesLevel : kFillWaves; }
+constexpr int kPriorityTurn = 13;    // log2 of the 100 MHz ticks a workgroup keeps the priority
 constexpr int kWalkThreads = 256;    // D-record walk back: 4 waves = 4 candidates per workgroup
 constexpr int kLdsStatic = 8192 + 256;    // the fill kernel's static LDS (entry tables, argmin)
 constexpr int kLdsBytes = 160 * 1024 - kLdsStatic;       // dynamic LDS a workgroup can get
@@ -798,9 +799,10 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 // `pitch` is the record's row pitch (elements per (k, l) row).
 template <bool kLevel, int kPath, bool kNarrow, bool kBlocks>
 __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void dp_fill(
-    ErrSource src, const int32_t *__restrict__ meta, LevelTables tables, int K, int L, int S,
-    int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec, float *__restrict__ rows,
-    int32_t *__restrict__ tstar, float *__restrict__ cost, Resume resume, Blocks blocks)
+    ErrSource src, const int32_t *__restrict__ meta, LevelTables tables, int units, int K, int L,
+    int S, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
+    float *__restrict__ rows, int32_t *__restrict__ tstar, float *__restrict__ cost, Resume resume,
+    Blocks blocks)
 {
     extern __shared__ float lds[];
     __shared__ float s_best[kMaxFillWaves];
@@ -925,7 +927,18 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     // chunk boundaries of this wave
     const int32_t *range = meta + kMetaHeader + 2 * L + (size_t)lb * kRangeStride + wv;
     int c_next = range[0], c_end_next = range[1];
+    // Two workgroups share a compute unit, and the hardware serves the older one first: left
+    // alone, the first `units` workgroups of a launch run at full speed, the second `units` on what
+    // is left and then by themselves, at barely more than half the unit's LDS rate.  The
+    // instruction priority therefore alternates between the two halves of each 2 * units
+    // workgroups with the wall clock (100 MHz; 2^13 ticks = 82 us per turn), so both advance
+    // alike and finish together.
+    const unsigned turn = ((unsigned)blockIdx.x / (unsigned)units) & 1u;
     for (int l = lb; l < le; ++l) {
+        if ((turn ^ (unsigned)(wall_clock64() >> kPriorityTurn)) & 1u)
+            __builtin_amdgcn_s_setprio(1);
+        else
+            __builtin_amdgcn_s_setprio(0);
         LevelEntry first = next_first;
         if constexpr (kNarrow) {
             first.shift = next_fetch.shift;
@@ -1321,14 +1334,14 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
                            B, waves, max_group, lds_small, lds_large, kLevel ? 0 : 1, meta, shifts,
                            order, start, entry);
     const LevelTables tables{shifts, order, start, entry, s8};
-    hipLaunchKernelGGL(in_place, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, tables, K,
-                       L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
+    hipLaunchKernelGGL(in_place, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, tables,
+                       units, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     if (lds_large)
         hipLaunchKernelGGL(two_rows, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, tables,
-                           K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
+                           units, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     if (in_memory)
-        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, src, meta, tables, K, L,
-                           S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
+        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, src, meta, tables, units,
+                           K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     return launch_status();
 }
 
