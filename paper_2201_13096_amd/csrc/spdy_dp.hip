@@ -797,7 +797,7 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 //   kBlocks  : the checkpoint / block passes of the small-record solve (D record only); the
 //              plain instantiation ignores `blocks`
 // `pitch` is the record's row pitch (elements per (k, l) row).
-template <bool kLevel, int kPath, bool kNarrow, bool kBlocks>
+template <bool kLevel, int kPath, bool kNarrow, bool kBlocks, bool kTurns = false>
 __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void dp_fill(
     ErrSource src, const int32_t *__restrict__ meta, LevelTables tables, int units, int K, int L,
     int S, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
@@ -930,15 +930,27 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     // Two workgroups share a compute unit, and the hardware serves the older one first: left
     // alone, the first `units` workgroups of a launch run at full speed, the second `units` on what
     // is left and then by themselves, at barely more than half the unit's LDS rate.  The
-    // instruction priority therefore alternates between the two halves of each 2 * units
+    // instruction priority therefore alternates between the two halves of the last 2 * units
     // workgroups with the wall clock (100 MHz; 2^13 ticks = 82 us per turn), so both advance
-    // alike and finish together.
+    // alike and finish together.  Earlier workgroups of a longer launch are left alone: a
+    // compute unit then always holds an older and a younger one, and a new one takes over when
+    // the older is done.  A launch with no more workgroups than compute units has no pairs.
+    // (kTurns: a separate instantiation, launched for batches of one or two rounds of
+    // workgroups; the other one is exactly the code without any of this.)
     const unsigned turn = ((unsigned)blockIdx.x / (unsigned)units) & 1u;
+    const int nwg = (K + teams - 1) / teams;
+    const bool take_turns = kTurns && nwg > units && (long long)blockIdx.x + 2 * units >= nwg;
+    unsigned long long now = take_turns ? wall_clock64() : 0;
     for (int l = lb; l < le; ++l) {
-        if ((turn ^ (unsigned)(wall_clock64() >> kPriorityTurn)) & 1u)
-            __builtin_amdgcn_s_setprio(1);
-        else
-            __builtin_amdgcn_s_setprio(0);
+        if constexpr (kTurns) {
+            if (take_turns) {
+                if ((turn ^ (unsigned)(now >> kPriorityTurn)) & 1u)
+                    __builtin_amdgcn_s_setprio(1);
+                else
+                    __builtin_amdgcn_s_setprio(0);
+                now = wall_clock64();            // read now, looked at a layer later: no wait
+            }
+        }
         LevelEntry first = next_first;
         if constexpr (kNarrow) {
             first.shift = next_fetch.shift;
@@ -1314,7 +1326,18 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     const int lds_large = need <= (size_t)kLdsHalf ? 0
                           : (need <= (size_t)kLdsBytes ? (int)need : kLdsBytes);
     const bool in_memory = need > (size_t)kLdsBytes;      // implies lay.may_spill
-    auto in_place = dp_fill<kLevel, 1, kNarrow, kBlocks>;
+    // workgroups the chip holds at once: two per compute unit for either variant
+    int device = 0, units = 0;
+    if (hipGetDevice(&device) != hipSuccess ||
+        hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess ||
+        units <= 0)
+        return SPDY_DP_ERR_LAUNCH;
+    // Workgroups that take turns at the priority pay off when a launch is one or two rounds of
+    // workgroups (measured: K = 4 x units 4 % faster, 16 x units no gain and a slightly slower
+    // kernel), and need pairs of workgroups to begin with.
+    const bool turns = K > units && (long long)K <= 4LL * units;
+    auto in_place = turns ? dp_fill<kLevel, 1, kNarrow, kBlocks, true>
+                          : dp_fill<kLevel, 1, kNarrow, kBlocks, false>;
     auto two_rows = dp_fill<kLevel, 2, kNarrow, kBlocks>;
     auto in_global = dp_fill<kLevel, 0, kNarrow, kBlocks>;
     // always the same limit, so that calls from several host threads cannot undo each other's
@@ -1323,12 +1346,6 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
         return SPDY_DP_ERR_LAUNCH;
 
-    // workgroups the chip holds at once: two per compute unit for either variant
-    int device = 0, units = 0;
-    if (hipGetDevice(&device) != hipSuccess ||
-        hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess ||
-        units <= 0)
-        return SPDY_DP_ERR_LAUNCH;
     if (!(kBlocks && blocks.pass == 1))          // the block passes reuse pass 0's tables
         hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, K, 2 * units, L, S, s8,
                            B, waves, max_group, lds_small, lds_large, kLevel ? 0 : 1, meta, shifts,
