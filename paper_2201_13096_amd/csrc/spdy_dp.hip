@@ -796,6 +796,8 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 //              two ways of loading do not meet in one control-flow join)
 //   kBlocks  : the checkpoint / block passes of the small-record solve (D record only); the
 //              plain instantiation ignores `blocks`
+//   kTurns   : the workgroups that share a compute unit take turns at the instruction priority
+//              (see the layer loop); `units` is the number of compute units
 // `pitch` is the record's row pitch (elements per (k, l) row).
 template <bool kLevel, int kPath, bool kNarrow, bool kBlocks, bool kTurns = false>
 __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void dp_fill(
