@@ -147,6 +147,9 @@ EDGE_SHAPES = [
     # more candidates than the chip holds at once: several teams per workgroup, the last
     # workgroup partly filled
     (1100, 4, 5, 700), (2600, 3, 6, 1500), (4100, 3, 4, 500),
+    # one or two workgroups per compute unit: the instantiation whose workgroups take turns at
+    # the instruction priority
+    (300, 4, 5, 700), (700, 3, 6, 1500), (1024, 3, 4, 500),
 ]
 
 
