@@ -82,6 +82,17 @@ def executed_updates_level_record(tau: np.ndarray, err: np.ndarray, B: int) -> i
     return total
 
 
+def host_cpu_model() -> str:
+    try:
+        with open("/proc/cpuinfo") as f:
+            for line in f:
+                if line.startswith("model name"):
+                    return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -236,7 +247,8 @@ def main() -> int:
     torch.cuda.synchronize()
     t1 = time.perf_counter()
     ms_per_step = (t1 - t0) * 1e3 / args.steps
-    fill_ms = float(np.mean([a.elapsed_time(b) for a, b in evs if a is not None]))
+    fill_samples = [a.elapsed_time(b) for a, b in evs if a is not None]
+    fill_ms = float(np.mean(fill_samples))
 
     nominal = K * L * S * B
     if args.record == "d":
@@ -279,6 +291,8 @@ def main() -> int:
             "frac": achieved / ALU_PEAK_LANE_OPS,
             "lane_ops_per_update": ops,
             "kernel_ms": fill_ms,
+            "kernel_ms_median": float(np.median(fill_samples)),
+            "kernel_ms_min": float(np.min(fill_samples)),
             "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, args.record))
             if K == cfg.K else None,
         },
@@ -289,6 +303,9 @@ def main() -> int:
             "frac": lds_achieved / LDS_PEAK_BYTES,
         },
     }
+
+    if out["roofline"]["traffic"] is not None:    # the record stream, not the bound
+        out["roofline"]["hbm_gbps"] = out["roofline"]["traffic"] / (fill_ms * 1e-3) / 1e9
 
     if not args.no_cpu_baseline:
         import oracle
@@ -310,6 +327,7 @@ def main() -> int:
             "sample": f"first {n} of {K} candidates of {cfg.name}, {threads} threads; "
                       f"one candidate on one thread took {t_one * 1e3:.1f} ms",
             "single_thread_ms_per_candidate": t_one * 1e3,
+            "cpu": host_cpu_model(),
         }
         out["parity"] = bool((p_gpu[:n] == p_ref).all() and
                              (c_gpu[:n].view(np.uint32) == c_ref.view(np.uint32)).all())
