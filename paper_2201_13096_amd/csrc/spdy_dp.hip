@@ -26,8 +26,11 @@
 //   * the waves of a workgroup are split at run time into teams, one candidate per team, so
 //     that each wave owns as many chunks as its registers hold whatever the reduced row length
 //     is; when every wave holds all its chunks of the row in registers the row is updated in
-//     place (one row per candidate), otherwise two rows alternate.
-// When not even one reduced row fits in LDS the same kernel runs with the rows in global memory.
+//     place (one row per candidate), otherwise two rows alternate;
+//   * two workgroups share a compute unit, and in a launch of one or two rounds of workgroups
+//     they take turns at the instruction priority, so that neither runs on the other's leftovers
+//     and then alone.
+// When two reduced rows do not fit in LDS the same kernel runs with the rows in global memory.
 #include <hip/hip_runtime.h>
 
 #include <stdint.h>
