@@ -46,6 +46,15 @@ constexpr int kWave = 64;            // lanes per wavefront = buckets per chunk
 // chunks each (value and level per chunk).
 constexpr int kMaxGroup = 26;        // most chunks a wave keeps in registers at once (D record)
 constexpr int kMaxGroupLevel = 10;   // same when the level is tracked too
+// In the instantiation for small batches (kTurns) a wave keeps up to 28: a row of 105 - 112
+// chunks (the paper's own sizes, T = 10^4) then still splits into two teams of four waves.  The
+// other instantiation stays at 26: with 28 its inner loops are the same instruction for
+// instruction, but stress_k256 ran 5 % slower (code placement), and long launches gain nothing.
+constexpr int kMaxGroupTurns = 28;
+template <bool kLevel, bool kTurns> constexpr int group_limit()
+{
+    return kLevel ? kMaxGroupLevel : (kTurns ? kMaxGroupTurns : kMaxGroup);
+}
 constexpr int kFillWaves = 8;        // waves of a fill workgroup (D record)
 constexpr int kFillWavesLevel = 16;  // (level record)
 constexpr int kMaxFillWaves = 16;
@@ -55,12 +64,12 @@ constexpr int kWalkThreads = 256;    // D-record walk back: 4 waves = 4 candidat
 constexpr int kLdsStatic = 8192 + 256;    // the fill kernel's static LDS (entry tables, argmin)
 constexpr int kLdsBytes = 160 * 1024 - kLdsStatic;       // dynamic LDS a workgroup can get
 constexpr int kLdsHalf = 80 * 1024 - kLdsStatic;         // lets two workgroups share a compute unit
-constexpr int kHalo = kMaxGroup * kWave;  // +inf apron left of every row (one group width)
+constexpr int kHalo = kMaxGroupTurns * kWave;  // +inf apron left of every row (a group's width)
 // The longest row the waves of a workgroup can hold in registers (and so update in place), with
 // its apron, fits the smaller LDS allocation for either record, and two rows that are any longer
 // do not: the in-place case and the launch with the smaller allocation coincide.
 constexpr bool kInPlaceFits =
-    (kFillWaves * kMaxGroup * kWave + kHalo) * 4 <= kLdsHalf &&
+    (kFillWaves * kMaxGroupTurns * kWave + kHalo) * 4 <= kLdsHalf &&
     (kFillWavesLevel * kMaxGroupLevel * kWave + kHalo) * 4 <= kLdsHalf &&
     2 * (kFillWaves * kMaxGroup * kWave + kWave + kHalo) * 4 > kLdsHalf &&
     2 * (kFillWavesLevel * kMaxGroupLevel * kWave + kWave + kHalo) * 4 > kLdsHalf;
@@ -119,7 +128,7 @@ Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes, long long
         lay.status = SPDY_DP_ERR_LEVELS;
         return lay;
     }
-    if (B > INT32_MAX - 2 * kWave * kMaxGroup) {   // bucket indices are int32 on the device
+    if (B > INT32_MAX - 2 * kWave * kMaxGroupTurns) {   // bucket indices are int32 on the device
         lay.status = SPDY_DP_ERR_OVERFLOW;
         return lay;
     }
@@ -719,7 +728,7 @@ __device__ __forceinline__ void fill_group(const float *prev, float *cur, uint8_
     }
 }
 
-template <bool kLevel, bool inplace>
+template <bool kLevel, bool inplace, int kMax>
 __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cur, uint8_t *choice,
                                              float *rec, LevelEntry first, LayerTable tl,
                                              ErrRow er, int s8, int t0, int lane, Pending pending)
@@ -727,8 +736,9 @@ __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cu
     switch (r) {
 #define SPDY_CASE(RR)                                                                          \
     case RR:                                                                                   \
-        fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, tl, er, s8, t0, lane,   \
-                                        pending);                                              \
+        if constexpr (RR <= kMax)                                                              \
+            fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, tl, er, s8, t0,     \
+                                            lane, pending);                                    \
         break;
         SPDY_CASE(0)
         SPDY_CASE(1)
@@ -744,7 +754,7 @@ __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cu
 #undef SPDY_CASE
 #define SPDY_CASE(RR)                                                                          \
     case RR:                                                                                   \
-        if constexpr (!kLevel)                                                                 \
+        if constexpr (RR <= kMax)                                                              \
             fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, tl, er, s8, t0,     \
                                             lane, pending);                                    \
         break;
@@ -764,6 +774,8 @@ __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cu
         SPDY_CASE(24)
         SPDY_CASE(25)
         SPDY_CASE(26)
+        SPDY_CASE(27)
+        SPDY_CASE(28)
 #undef SPDY_CASE
     }
 }
@@ -997,17 +1009,17 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
         }
         const LayerTable tl = tables.layer(l);
         const ErrRow er = mine.layer(l, S);
-        constexpr int kMax = kLevel ? kMaxGroupLevel : kMaxGroup;
+        constexpr int kMax = group_limit<kLevel, kTurns>();
         const Pending pending{&next_fetch, &next_first};
         if constexpr (inplace) {                 // c_end - c <= kMax by construction
-            fill_group_n<kLevel, true>(min(c_end - c, kMax), prev, cur, choice_l, drec_l, first,
+            fill_group_n<kLevel, true, kMax>(min(c_end - c, kMax), prev, cur, choice_l, drec_l, first,
                                        tl, er, s8, c * kWave, lane, pending);
         } else {
             while (c < c_end) {
                 const int n = c_end - c;
                 const int groups = (n + kMax - 1) / kMax;
                 const int r = (n + groups - 1) / groups;
-                fill_group_n<kLevel, false>(r, prev, cur, choice_l, drec_l, first, tl, er, s8,
+                fill_group_n<kLevel, false, kMax>(r, prev, cur, choice_l, drec_l, first, tl, er, s8,
                                             c * kWave, lane, pending);
                 c += r;
             }
@@ -1323,14 +1335,6 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     // others return at once.  A row that the waves of a workgroup can hold in registers is
     // updated in place whatever the reduced length turns out to be, so one row bounds the need;
     // otherwise two rows alternate.
-    const int waves = nchunks < fill_waves<kLevel>() ? nchunks : fill_waves<kLevel>();
-    const int max_group = kLevel ? kMaxGroupLevel : kMaxGroup;
-    const size_t row_bytes = (lay.row + kHalo) * sizeof(float);
-    const size_t need = (long long)nchunks <= (long long)waves * max_group ? row_bytes : 2 * row_bytes;
-    const int lds_small = kLdsHalf;
-    const int lds_large = need <= (size_t)kLdsHalf ? 0
-                          : (need <= (size_t)kLdsBytes ? (int)need : kLdsBytes);
-    const bool in_memory = need > (size_t)kLdsBytes;      // implies lay.may_spill
     // workgroups the chip holds at once: two per compute unit for either variant
     int device = 0, units = 0;
     if (hipGetDevice(&device) != hipSuccess ||
@@ -1341,6 +1345,14 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     // workgroups (measured: K = 4 x units 4 % faster, 16 x units no gain and a slightly slower
     // kernel), and need pairs of workgroups to begin with.
     const bool turns = K > units && (long long)K <= 4LL * units;
+    const int waves = nchunks < fill_waves<kLevel>() ? nchunks : fill_waves<kLevel>();
+    const int max_group = turns ? group_limit<kLevel, true>() : group_limit<kLevel, false>();
+    const size_t row_bytes = (lay.row + kHalo) * sizeof(float);
+    const size_t need = (long long)nchunks <= (long long)waves * max_group ? row_bytes : 2 * row_bytes;
+    const int lds_small = kLdsHalf;
+    const int lds_large = need <= (size_t)kLdsHalf ? 0
+                          : (need <= (size_t)kLdsBytes ? (int)need : kLdsBytes);
+    const bool in_memory = need > (size_t)kLdsBytes;      // implies lay.may_spill
     auto in_place = turns ? dp_fill<kLevel, 1, kNarrow, kBlocks, true>
                           : dp_fill<kLevel, 1, kNarrow, kBlocks, false>;
     auto two_rows = dp_fill<kLevel, 2, kNarrow, kBlocks>;

@@ -80,7 +80,7 @@ def test_workspace_size(binding):
     row = (B + 1 + 63) // 64 * 64
     full = binding.spdy_dp_workspace_bytes(K, L, S, B)
     auto = binding.spdy_dp_workspace_bytes_checkpointed(K, L, S, B, 0)      # stride 15
-    spill = 2 * K * (row + 1664) * 4            # two rows per candidate in memory (long rows)
+    spill = 2 * K * (row + 1792) * 4            # two rows per candidate in memory (long rows)
     assert 4 * K * (13 + 15) * row + spill <= auto <= 4 * K * (13 + 15) * row + spill + (1 << 20)
     assert auto * 5 < full
     assert binding.spdy_dp_workspace_bytes_checkpointed(K, L, S, B, 10) == \
