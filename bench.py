@@ -115,6 +115,9 @@ def main() -> int:
     ap.add_argument("--overlap", action="store_true",
                     help="pipeline consecutive steps over two streams and two workspaces: the "
                          "walk back of step i runs beside the fill of step i + 1")
+    ap.add_argument("--one-call", action="store_true",
+                    help="time spdy_dp_solve_batched as one call instead of its two stages "
+                         "(no fill-stage events, so no roofline objects)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for "
@@ -214,6 +217,13 @@ def main() -> int:
             if ev_a is not None:
                 ev_a.record()
             dp.spdy_dp_solve_from_incumbent(tau_d, err_d, first_d, B, inc_ws, profile, cost, ws)
+            if ev_b is not None:
+                ev_b.record()
+            return
+        if args.one_call:
+            if ev_a is not None:
+                ev_a.record()
+            dp.spdy_dp_solve_batched(tau_d, err_d, B, profile, cost, ws)
             if ev_b is not None:
                 ev_b.record()
             return
@@ -336,10 +346,15 @@ def main() -> int:
         out["config"]["workload"] = f"{cfg.name}+checkpoints(stride={args.checkpoints})"
         out["config"]["workspace_bytes"] = int(ws.numel())
         out["config"]["workspace_bytes_full_record"] = int(dp.spdy_dp_workspace_bytes(K, L, S, B))
+    if args.one_call:
+        out.pop("roofline", None)
+        out.pop("roofline_lds", None)
+        out["config"]["workload"] = cfg.name + "+one_call"
     if first_layer is not None:
         # the roofline objects describe the plain fill; here the event pair spans the whole call
         # and a varying part of the updates is skipped
-        del out["roofline"], out["roofline_lds"]
+        out.pop("roofline", None)
+        out.pop("roofline_lds", None)
         out["config"]["workload"] = f"{cfg.name}+from_incumbent(d={args.from_incumbent})"
         out["config"]["mean_first_layer"] = float(first_layer.mean())
     print(json.dumps(out))
