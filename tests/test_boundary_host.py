@@ -175,3 +175,50 @@ def test_binding_refuses_cpu_tensors(binding):
     err = torch.zeros((1, 2, 2), dtype=torch.float32)
     with pytest.raises(TypeError):
         binding.spdy_dp_solve_batched(tau, err, 4)
+
+
+def test_executed_update_counts_bracket_the_necessary_work():
+    """The roofline's numerator is the update count bench.py derives from tau.  It must cover every
+    update Alg. 1 needs (a finite D_{l-1}[t - tau] that can still end within the budget) and may
+    not exceed Alg. 1's own loop trips; folding levels of equal time can only lower it."""
+    import numpy as np
+    import bench
+    import oracle
+    import workloads
+    rng = np.random.default_rng(5)
+    for case in range(12):
+        L = int(rng.integers(1, 7))
+        S = int(rng.integers(1, 9))
+        B = int(rng.choice([0, 9, 40, 150]))
+        tau, err, _ = workloads.random_instance(rng, 2, L, S, B, tau_max=max(1, B // 2),
+                                                zero_tau_frac=0.2, integer_err=3,
+                                                layer_floor=int(rng.choice([0, 3])))
+        D, _, _, _ = oracle.tables_ref(tau, err[0], B)
+        t = tau.astype(np.int64)
+        mn = t.min(axis=1)
+        rest = np.concatenate([np.cumsum(mn[::-1])[::-1][1:], [0]])   # least time still to come
+        needed = 0
+        for l in range(L):
+            prev = D[l - 1] if l > 0 else np.r_[0.0, np.full(B, np.inf)]
+            for s in range(S):
+                for u in range(B + 1):
+                    tt = u + t[l, s]
+                    if np.isfinite(prev[u]) and tt + rest[l] <= B:
+                        needed += 1
+        nominal = sum(max(0, B + 1 - int(t[l, s])) for l in range(L) for s in range(S))
+        plain = bench.executed_updates_per_candidate(tau, B, False)
+        folded = bench.executed_updates_per_candidate(tau, B, True)
+        skipped = bench.executed_updates_level_record(tau, err, B)
+        assert folded <= plain <= nominal, (case, folded, plain, nominal)
+        assert 2 * folded <= skipped <= 2 * plain, (case, folded, skipped, plain)
+        # every needed update is executed; with equal times folded, one update serves all levels
+        # of a time, so compare per distinct time
+        needed_folded = 0
+        for l in range(L):
+            prev = D[l - 1] if l > 0 else np.r_[0.0, np.full(B, np.inf)]
+            for d in sorted(set(int(x) for x in t[l])):
+                for u in range(B + 1):
+                    if np.isfinite(prev[u]) and u + d + rest[l] <= B:
+                        needed_folded += 1
+        assert needed <= plain, (case, needed, plain)
+        assert needed_folded <= folded, (case, needed_folded, folded)
