@@ -79,6 +79,7 @@ constexpr unsigned kNoLevel = 0xFF;
 constexpr size_t kAlign = 256;
 constexpr int kMetaHeader = 8;       // int32 words before the per-layer arrays
 // meta: header | m_l [L] | chunks of row l [L] | chunk boundaries of the team waves [L][stride]
+//       | largest usable shift of layer l [L]
 constexpr int kRangeStride = kMaxFillWaves + 1;
 
 // kMetaPath: 0 = rows in global memory, 1 / 2 = rows in LDS, fill kernel launched with the
@@ -100,7 +101,7 @@ struct Layout {
     size_t row;          // buckets per padded row for the full budget (multiple of 64)
     bool may_spill;      // rows of the full budget may exceed LDS: the global-row launch is needed
     size_t s8;           // levels per layer padded to a multiple of kBatch
-    size_t meta_off;     // int32 meta[kMetaHeader + (2 + kRangeStride) L]
+    size_t meta_off;     // int32 meta[kMetaHeader + (3 + kRangeStride) L]
     size_t shifts_off;   // int32 shifts[L][s8]: tau - m_l of the r-th visited entry
     size_t order_off;    // int32 order[L][s8]: level index at position r of the visiting order
     size_t start_off;    // int32 start[L][s8 + kBatch]: first position of entry r (D record)
@@ -145,7 +146,7 @@ Layout make_layout(int K, int L, int S, int B, size_t workspace_bytes, long long
     lay.s8 = align_up((size_t)S, kBatch);
     lay.meta_off = 0;
     lay.shifts_off =
-        align_up((kMetaHeader + (2 + (size_t)kRangeStride) * L) * sizeof(int32_t), kAlign);
+        align_up((kMetaHeader + (3 + (size_t)kRangeStride) * L) * sizeof(int32_t), kAlign);
     lay.order_off = align_up(lay.shifts_off + (size_t)L * lay.s8 * sizeof(int32_t), kAlign);
     lay.start_off = align_up(lay.order_off + (size_t)L * lay.s8 * sizeof(int32_t), kAlign);
     lay.entry_off =
@@ -294,6 +295,7 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots
             }
         }
         nact[l] = span;
+        meta[kMetaHeader + (2 + (size_t)kRangeStride) * L + l] = span;
         local += span;
     }
     long long h = 0;                              // sum of the slices before this thread's
@@ -502,14 +504,23 @@ struct LayerTable {
     const int32_t *order;   // [s8]
     const int32_t *start;   // [s8 + kBatch], D record only
     const int32_t *entry;   // [s8], D record only
+    int limit;              // a larger shift than this (the reduced budget) is never usable
+    // An entry beyond the budget could still "apply" to the padding buckets at the end of a row;
+    // it is taken out here, so that every shift the sweep uses is at most the layer's largest
+    // usable one (the staged tiles of the global-row path size their window by that).
+    __device__ __forceinline__ int32_t usable(int32_t shift) const
+    {
+        return shift > limit ? INT32_MAX : shift;
+    }
 };
 struct LevelTables {
     const int32_t *shifts, *order, *start, *entry;
     int s8;
+    int limit = INT32_MAX;  // set by the fill once it knows the reduced budget
     __device__ __forceinline__ LayerTable layer(int l) const
     {
         return LayerTable{shifts + (size_t)l * s8, order + (size_t)l * s8,
-                          start + (size_t)l * (s8 + kBatch), entry + (size_t)l * s8};
+                          start + (size_t)l * (s8 + kBatch), entry + (size_t)l * s8, limit};
     }
 };
 
@@ -524,7 +535,7 @@ __device__ __forceinline__ LevelEntry load_level(LayerTable tl, ErrRow er, int s
     p.err = __builtin_inff();
     const int r = blk + lane;
     if (r < s8) {
-        p.shift = tl.shift[r];
+        p.shift = tl.usable(tl.shift[r]);
         if constexpr (kLevel) {
             p.err = er.at(tl.order[r]);
         } else {
@@ -556,7 +567,7 @@ __device__ __forceinline__ LevelFetch fetch_levels(LayerTable tl, ErrRow er, int
                                                    int lane, bool producer)
 {
     LevelFetch f;
-    f.shift = lane < s8 ? tl.shift[lane] : INT32_MAX;
+    f.shift = lane < s8 ? tl.usable(tl.shift[lane]) : INT32_MAX;
     f.raw = __builtin_inff();
     f.entry = 0;
     if (lane < S && (kLevel || producer)) {
@@ -837,6 +848,7 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
             write_result(__builtin_inff(), 0, blockIdx.x, tstar, cost);
         return;
     }
+    tables.limit = kPath == 0 ? bp : INT32_MAX;  // only the tiles of path 0 depend on it
     const int teams = meta[kMetaTeams];
     const int tw = meta[kMetaTeamWaves];
     if ((long long)blockIdx.x * teams >= K)
@@ -1015,13 +1027,59 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
             fill_group_n<kLevel, true, kMax>(min(c_end - c, kMax), prev, cur, choice_l, drec_l, first,
                                        tl, er, s8, c * kWave, lane, pending);
         } else {
-            while (c < c_end) {
-                const int n = c_end - c;
-                const int groups = (n + kMax - 1) / kMax;
-                const int r = (n + groups - 1) / groups;
-                fill_group_n<kLevel, false, kMax>(r, prev, cur, choice_l, drec_l, first, tl, er, s8,
-                                            c * kWave, lane, pending);
-                c += r;
+            // Rows in global memory: the row is computed in tiles of at most kMax chunks per
+            // wave, and the part of the previous row a tile reads (the tile itself and the
+            // layer's largest usable shift to its left) is first copied to LDS, so the sweep
+            // reads LDS as in the resident case.  One candidate per workgroup here, so every
+            // wave takes the same number of trips.  A layer whose largest shift leaves no room
+            // for a tile is swept from global memory.
+            int tile = 0, span = 0;
+            if constexpr (kPath == 0) {
+                span = meta[kMetaHeader + (2 + (size_t)kRangeStride) * L + l];
+                tile = (kLdsBytes / (int)sizeof(float) - span - 4) / kWave / tw * tw;
+                tile = min(tile, tw * kMax);
+            }
+            if (kPath == 0 && tile >= tw) {
+                const int n_l = (active && l >= l0) ? nact[l] : 0;
+                if (n_l == 0)
+                    pending.settle();
+                for (int c0 = 0; c0 < n_l; c0 += tile) {
+                    const int nt = min(tile, n_l - c0);
+                    // (lo a multiple of four floats: rows and aprons are, so the copy moves 16
+                    // bytes per lane, eight loads in flight per lane)
+                    const int lo = max((c0 * kWave - span) & ~3, -kHalo);
+                    const int len4 = ((c0 + nt) * kWave - lo) / 4;
+                    const float4 *from = reinterpret_cast<const float4 *>(prev + lo);
+                    float4 *to = reinterpret_cast<float4 *>(lds);
+                    for (int i0 = 0; i0 < len4; i0 += 8 * nthreads) {
+                        float4 v[8];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j)   // (past the end: the last element again)
+                            v[j] = from[min(i0 + j * nthreads + tid, len4 - 1)];
+#pragma unroll
+                        for (int j = 0; j < 8; ++j) {
+                            const int i = i0 + j * nthreads + tid;
+                            if (i < len4)
+                                to[i] = v[j];
+                        }
+                    }
+                    __syncthreads();
+                    const int cb = c0 + (int)((long long)wv * nt / tw);
+                    const int ce = c0 + (int)((long long)(wv + 1) * nt / tw);
+                    fill_group_n<kLevel, false, kMax>(ce - cb, lds - lo, cur, choice_l, drec_l,
+                                                      first, tl, er, s8, cb * kWave, lane,
+                                                      pending);
+                    __syncthreads();             // the next tile overwrites the staged part
+                }
+            } else {
+                while (c < c_end) {
+                    const int n = c_end - c;
+                    const int groups = (n + kMax - 1) / kMax;
+                    const int r = (n + groups - 1) / groups;
+                    fill_group_n<kLevel, false, kMax>(r, prev, cur, choice_l, drec_l, first, tl,
+                                                      er, s8, c * kWave, lane, pending);
+                    c += r;
+                }
             }
         }
         // the table of the next layer; the barrier that ends this layer publishes it
@@ -1362,6 +1420,10 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
         hipFuncSetAttribute(reinterpret_cast<const void *>(two_rows),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
         return SPDY_DP_ERR_LAUNCH;
+    if (in_memory &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(in_global),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
+        return SPDY_DP_ERR_LAUNCH;
 
     if (!(kBlocks && blocks.pass == 1))          // the block passes reuse pass 0's tables
         hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, K, 2 * units, L, S, s8,
@@ -1374,8 +1436,8 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
         hipLaunchKernelGGL(two_rows, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, tables,
                            units, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     if (in_memory)
-        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), 0, q, src, meta, tables, units,
-                           K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
+        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), kLdsBytes, q, src, meta, tables,
+                           units, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     return launch_status();
 }
 

@@ -142,7 +142,8 @@ EDGE_SHAPES = [
     (3, 1, 1, 0), (2, 1, 5, 7), (4, 5, 1, 100), (5, 6, 7, 63), (5, 6, 7, 64), (3, 9, 12, 1000),
     (7, 12, 33, 2500), (2, 4, 255, 700), (3, 17, 40, 10000), (2, 20, 16, 16384),
     (2, 7, 9, 17599), (2, 6, 10, 17600),             # around the largest rows that fit LDS
-    (3, 6, 10, 20480), (2, 5, 12, 33000), (1, 4, 6, 70001),   # rows in global memory
+    (3, 6, 10, 20480), (2, 5, 12, 33000), (1, 4, 6, 70001),   # rows in global memory, tiles
+    (1, 2, 5, 70001),     # ... and shifts too long for a tile's window in LDS
     (2, 300, 3, 500),                                # more layers than prepare threads
     (2, 5, 64, 300), (2, 5, 65, 300), (3, 4, 129, 900),       # level-block boundaries
     (37, 4, 5, 200), (19, 3, 6, 1500),               # few candidates: one team per workgroup
