@@ -206,7 +206,9 @@ __device__ __forceinline__ long long block_scan_256(long long v, long long *part
 // reduced time after layer l is sum_{j<=l} max_s (tau[j][s] - m_j) over the levels that fit the
 // reduced budget).  It also picks the path: which launch of the fill kernel (LDS allocation
 // lds_small or lds_large bytes, `waves` waves per workgroup) fits, into how many teams its waves
-// split, and whether one row per candidate is enough.  Thread i owns a slice of layers.
+// split, and whether one row per candidate is enough; and it records each layer's largest usable
+// shift (the tiles of the global-row path size their window in LDS by it).  Thread i owns a slice
+// of layers.
 __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots, int L, int S,
                                int B, int waves, int max_group, int lds_small, int lds_large,
                                int32_t *__restrict__ meta)
