@@ -63,7 +63,7 @@ def check_tables(dp, tau, err_k, B, ws, k, K):
     L, S = tau.shape
     D, P, prof, cost = oracle.tables_ref(tau, err_k, B)
     lay = dp.spdy_dp_workspace_layout(K, L, S, B, ws.numel())
-    meta = ws[lay["meta_offset"]:lay["meta_offset"] + 4 * (8 + 2 * L)].cpu().numpy().view(np.int32)
+    meta = ws[lay["meta_offset"]:lay["meta_offset"] + 4 * (8 + 20 * L)].cpu().numpy().view(np.int32)
     mn = tau.min(axis=1).astype(np.int64)
     M = int(mn.sum())
     tstar = ws[lay["tstar_offset"] + 4 * k:lay["tstar_offset"] + 4 * k + 4].cpu().numpy() \
@@ -75,6 +75,9 @@ def check_tables(dp, tau, err_k, B, ws, k, K):
     assert meta[0] == bp and meta[1] == M and meta[2] == (bp + 64) // 64 * 64
     assert (meta[8:8 + L] == mn).all()
     nact = meta[8 + L:8 + 2 * L].astype(np.int64)
+    # the largest usable shift of each layer (what a staged tile of the global-row path reaches)
+    delta = tau.astype(np.int64) - mn[:, None]
+    assert (meta[8 + 19 * L:8 + 20 * L] == np.where(delta <= bp, delta, 0).max(axis=1)).all()
     lo = np.cumsum(mn)
     pitch, rows = lay["record_pitch"], lay["record_rows"]
     esize = 4 if lay["variant"] == 0 else 1
