@@ -88,7 +88,8 @@ constexpr int kRangeStride = kMaxFillWaves + 1;
 // candidate suffices (written back between two barriers); otherwise two rows alternate.
 enum MetaWord {
     kMetaBudget = 0, kMetaMinTime = 1, kMetaRow = 2, kMetaPath = 3, kMetaTeamWaves = 4,
-    kMetaTeams = 5, kMetaInPlace = 6
+    kMetaTeams = 5, kMetaInPlace = 6,
+    kMetaStage = 7      // bytes of LDS the global-row launch has for the windows of its tiles
 };
 
 enum Variant { kValueRecord = 0, kLevelRecord = 1 };
@@ -211,7 +212,7 @@ __device__ __forceinline__ long long block_scan_256(long long v, long long *part
 // of layers.
 __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots, int L, int S,
                                int B, int waves, int max_group, int lds_small, int lds_large,
-                               int32_t *__restrict__ meta)
+                               int lds_stage, int32_t *__restrict__ meta)
 {
     __shared__ long long s_sum[8];
     __shared__ int s_budget, s_team_waves;
@@ -271,6 +272,7 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots
         meta[kMetaTeams] = teams;
         meta[kMetaTeamWaves] = waves / teams;
         meta[kMetaInPlace] = inplace;
+        meta[kMetaStage] = lds_stage;
         s_budget = bp;
         s_team_waves = waves / teams;
     }
@@ -396,7 +398,8 @@ __device__ void prepare_order(const int32_t *__restrict__ tau, int l, int S, int
 __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ tau, int K,
                                                   int slots, int L, int S,
                                                   int s8, int B, int waves, int max_group,
-                                                  int lds_small, int lds_large, int sorted,
+                                                  int lds_small, int lds_large, int lds_stage,
+                                                  int sorted,
                                                   int32_t *__restrict__ meta,
                                                   int32_t *__restrict__ shifts,
                                                   int32_t *__restrict__ order,
@@ -404,7 +407,8 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
                                                   int32_t *__restrict__ entry_of)
 {
     if (blockIdx.x == 0)
-        prepare_budget(tau, K, slots, L, S, B, waves, max_group, lds_small, lds_large, meta);
+        prepare_budget(tau, K, slots, L, S, B, waves, max_group, lds_small, lds_large, lds_stage,
+                       meta);
     else
         prepare_order(tau, blockIdx.x - 1, S, s8, sorted, shifts, order, start, entry_of);
 }
@@ -1038,7 +1042,7 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
             int tile = 0, span = 0;
             if constexpr (kPath == 0) {
                 span = meta[kMetaHeader + (2 + (size_t)kRangeStride) * L + l];
-                tile = (kLdsBytes / (int)sizeof(float) - span - 4) / kWave / tw * tw;
+                tile = (meta[kMetaStage] / (int)sizeof(float) - span - 4) / kWave / tw * tw;
                 tile = min(tile, tw * kMax);
             }
             if (kPath == 0 && tile >= tw) {
@@ -1422,6 +1426,10 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
         hipFuncSetAttribute(reinterpret_cast<const void *>(two_rows),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
         return SPDY_DP_ERR_LAUNCH;
+    // The global-row launch stages its tiles' windows in LDS: all of it with one workgroup per
+    // compute unit, half of it when there are candidates for two (one sweeps while the other
+    // copies).
+    const int lds_stage = K > units ? kLdsHalf : kLdsBytes;
     if (in_memory &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(in_global),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
@@ -1429,8 +1437,8 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
 
     if (!(kBlocks && blocks.pass == 1))          // the block passes reuse pass 0's tables
         hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, K, 2 * units, L, S, s8,
-                           B, waves, max_group, lds_small, lds_large, kLevel ? 0 : 1, meta, shifts,
-                           order, start, entry);
+                           B, waves, max_group, lds_small, lds_large, lds_stage, kLevel ? 0 : 1, meta,
+                           shifts, order, start, entry);
     const LevelTables tables{shifts, order, start, entry, s8};
     hipLaunchKernelGGL(in_place, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, tables,
                        units, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
@@ -1438,7 +1446,7 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
         hipLaunchKernelGGL(two_rows, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, tables,
                            units, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     if (in_memory)
-        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), kLdsBytes, q, src, meta, tables,
+        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), lds_stage, q, src, meta, tables,
                            units, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     return launch_status();
 }

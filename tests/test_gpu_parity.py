@@ -147,6 +147,7 @@ EDGE_SHAPES = [
     (2, 7, 9, 17599), (2, 6, 10, 17600),             # around the largest rows that fit LDS
     (3, 6, 10, 20480), (2, 5, 12, 33000), (1, 4, 6, 70001),   # rows in global memory, tiles
     (1, 2, 5, 70001),     # ... and shifts too long for a tile's window in LDS
+    (300, 3, 5, 22000),   # ... and two workgroups per compute unit with half-size windows
     (2, 300, 3, 500),                                # more layers than prepare threads
     (2, 5, 64, 300), (2, 5, 65, 300), (3, 4, 129, 900),       # level-block boundaries
     (37, 4, 5, 200), (19, 3, 6, 1500),               # few candidates: one team per workgroup
