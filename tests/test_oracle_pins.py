@@ -139,20 +139,111 @@ def test_continuous_errors_against_enumeration(seed):
 def test_integer_errors_pin_both_tie_breaks(seed):
     """Small integer errors: all sums exact, ties everywhere.  The oracle must return the
     optimal profile that is smallest under (cost, total time, s_L, s_{L-1}, .., s_1), which is
-    what "smallest level wins a cell" plus "smallest t wins the final argmin" imply."""
+    what "smallest level wins a cell" plus "smallest t wins the final argmin" imply.  Budgets are
+    drawn around the middle of the reachable times, so that they bind (with a slack budget two
+    tied profiles that differ in several layers always have a tied mixture that both ways of
+    reading the key agree on)."""
     rng = np.random.default_rng(200 + seed)
     n_tied = 0
     for _ in range(120):
         L, S = int(rng.integers(1, 7)), int(rng.integers(2, 7))
-        B = int(rng.integers(0, 50))
-        tau, err, _ = workloads.random_instance(rng, 1, L, S, B, tau_max=int(rng.integers(1, 12)),
+        tau, err, _ = workloads.random_instance(rng, 1, L, S, 10 ** 6,
+                                                tau_max=int(rng.integers(1, 12)),
                                                 integer_err=int(rng.integers(1, 4)))
+        lo, hi = int(tau.min(axis=1).sum()), int(tau.max(axis=1).sum())
+        B = int(rng.integers(lo, max(lo, (lo + hi) // 2) + 1))
         p, c = oracle.solve_ref(tau, err, B)
         bp, bc, bt, nb = oracle.brute_force(tau, err, B)
         assert c[0].tobytes() == bc.tobytes()
         assert p[0].tolist() == bp.tolist()
         n_tied += nb > 1
     assert n_tied > 40
+
+
+def load_golden_instances(path):
+    """Several instances per file: "instance NAME" starts one; case rows carry the number of tied
+    profiles before the levels."""
+    out, cur = [], None
+    with open(path) as f:
+        for line in f:
+            tok = line.split("#", 1)[0].split()
+            if not tok:
+                continue
+            if tok[0] == "instance":
+                cur = {"name": tok[1], "tau": [], "err": [], "cases": []}
+                out.append(cur)
+            elif tok[0] == "dims":
+                cur["dims"] = (int(tok[1]), int(tok[2]))
+            elif tok[0] == "tau":
+                cur["tau"].append([int(x) for x in tok[1:]])
+            elif tok[0] == "err":
+                cur["err"].append([float(x) for x in tok[1:]])
+            elif tok[0] == "case":
+                cur["cases"].append((int(tok[1]), float(tok[2]), int(tok[3]), int(tok[4]),
+                                     [int(x) for x in tok[5:]]))
+    for inst in out:
+        inst["tau"] = np.array(inst["tau"], dtype=np.int32)
+        inst["err"] = np.array(inst["err"], dtype=np.float32)
+        assert inst["tau"].shape == inst["dims"] and inst["err"].shape == inst["dims"]
+    return out
+
+
+def test_tied_optima_under_a_binding_budget(golden_dir):
+    """Hand-worked instances whose optimum is attained by several profiles that differ in two or
+    more layers while the budget binds: the dynamic program and the enumerator must both return
+    the tied profile that is smallest read from the LAST layer down (strict "<" per cell, walk
+    back from the last layer), which differs from the one smallest read from the first layer."""
+    instances = load_golden_instances(os.path.join(golden_dir, "tied_optima_binding_budget.txt"))
+    assert len(instances) >= 6
+    separating = 0
+    for inst in instances:
+        tau, err = inst["tau"], inst["err"]
+        for B, cost, t, n_tied, prof in inst["cases"]:
+            p, c = oracle.solve_ref(tau, err, B)
+            assert c[0] == F32(cost), (inst["name"], B, c)
+            assert p[0].tolist() == prof, (inst["name"], B, p)
+            bp, bc, bt, nb = oracle.brute_force(tau, err, B)
+            assert bc == F32(cost) and bt == t and nb == n_tied, (inst["name"], B, bc, bt, nb)
+            assert bp.tolist() == prof, (inst["name"], B, bp)
+            # the fixture itself against a plain enumeration written here
+            ec, et, winners = python_enumeration(tau, err, B)
+            assert len(winners) == n_tied and et == t
+            if winners:
+                assert tuple(prof) == min(winners, key=lambda q: tuple(reversed(q)))
+                separating += tuple(prof) != min(winners)
+    assert separating >= 12
+
+
+@pytest.mark.parametrize("seed", range(4))
+def test_tie_key_reads_from_the_last_layer(seed):
+    """Random small instances whose layers come in one or two KINDS (layers of a kind share their
+    times and errors, like the repeated blocks of a network), integer errors, binding budgets:
+    exchanging the levels of two layers of a kind keeps error and time, so tied optima that differ
+    in several layers are the rule.  Winners are listed by a plain Python enumeration; both the
+    dynamic program and the C enumerator must return the winner that is smallest read from the
+    last layer down, on many instances where reading from the first layer up picks another."""
+    rng = np.random.default_rng(900 + seed)
+    separating = 0
+    for _ in range(150):
+        L, S = int(rng.integers(2, 5)), int(rng.integers(2, 4))
+        kinds = int(rng.integers(1, 3))
+        tau_k, err_k, _ = workloads.random_instance(rng, 1, kinds, S, 10 ** 6,
+                                                    tau_max=int(rng.integers(1, 6)),
+                                                    integer_err=int(rng.integers(2, 4)))
+        kind = rng.integers(0, kinds, size=L)
+        tau = np.ascontiguousarray(tau_k[kind])
+        err = np.ascontiguousarray(err_k[:, kind])
+        lo, hi = int(tau.min(axis=1).sum()), int(tau.max(axis=1).sum())
+        B = int(rng.integers(lo, max(lo, (lo + hi) // 2) + 1))
+        cost, t, winners = python_enumeration(tau, err[0], B)
+        assert winners
+        want = min(winners, key=lambda q: tuple(reversed(q)))
+        p, c = oracle.solve_ref(tau, err, B)
+        bp, bc, bt, nb = oracle.brute_force(tau, err, B)
+        assert tuple(p[0].tolist()) == want and tuple(bp.tolist()) == want
+        assert c[0] == F32(cost) and bc == F32(cost) and bt == t and nb == len(winners)
+        separating += want != min(winners)
+    assert separating >= 6, separating
 
 
 def test_zero_times_over_budget_times_forbidden_levels_infeasible():
