@@ -50,9 +50,10 @@
  *     `stream` (a hipStream_t passed as void*, NULL = the default stream) and results are valid
  *     once the caller has synchronised that stream.  Calls on different streams must not share a
  *     workspace.
- *   - Arguments are validated on the host; on a negative return nothing was enqueued and no
- *     output was touched.  The CONTENTS of tau and err are not inspected (that would need a
- *     device-to-host copy): tau[l][s] < 0, err = NaN and err = -inf are undefined behaviour.
+ *   - Arguments are validated on the host; on a negative return other than SPDY_DP_ERR_LAUNCH
+ *     nothing was enqueued and no output was touched.  The CONTENTS of tau and err are not
+ *     inspected (that would need a device-to-host copy): tau[l][s] < 0, err = NaN and err = -inf
+ *     are undefined behaviour.
  *   - The device in use must be a gfx950; the current HIP device is used.
  */
 #ifndef SPDY_DP_H
@@ -72,7 +73,10 @@ extern "C" {
                                       reaches this cell"                                        */
 #define SPDY_DP_ERR_WORKSPACE (-4) /* workspace_bytes < spdy_dp_workspace_bytes_min(K,L,S,B)   */
 #define SPDY_DP_ERR_OVERFLOW (-5)  /* K * L * (B + 1) does not fit the index arithmetic         */
-#define SPDY_DP_ERR_LAUNCH (-9)    /* the HIP runtime refused a launch (see hipGetLastError)    */
+#define SPDY_DP_ERR_LAUNCH (-9)    /* the HIP runtime refused a query or a launch (see
+                                      hipGetLastError); unlike the argument errors above it can
+                                      come back after earlier kernels of the call were enqueued,
+                                      so the outputs are then undefined                          */
 
 /* Bytes of device workspace for the fast variant (fp32 D recorded per cell), or 0 if the sizes
  * are invalid.  About 4 * K * L * (B + 1) bytes, plus 8 * K * (B + 1) when two rows of B + 1 floats
@@ -174,16 +178,26 @@ int spdy_dp_solve_checkpointed(const int32_t *tau, const float *err, int K, int 
 /* Test/debug accessor: where things are in a workspace of `workspace_bytes` bytes.
  *   out[0] variant: 0 = fp32 D record, 1 = one-byte level record
  *   out[1] byte offset of the int32 header: [0] B - M (or -1 if M > B: nobody is feasible),
- *          [1] M, [2] reduced row length (B - M + 1 padded to 64), [3] 0 if the rows live in
- *          global memory, 1 or 2 if they live in LDS; then m_l at [8 + l] and the number of
- *          computed 64-bucket chunks of layer l at [8 + L + l]
+ *          [1] M, [2] reduced row length (B - M + 1 padded to 64), [3] which launch of the fill
+ *          did the work: 0 rows in global memory, 1 one row per candidate in LDS updated in
+ *          place, 2 two rows in LDS; [4] waves per candidate, [5] candidates per workgroup,
+ *          [6] 1 if rows are updated in place; and what that choice was made from: [7] bytes of
+ *          LDS for the windows of launch 0, [8] waves per workgroup, [9] most 64-bucket chunks a
+ *          wave keeps in registers, [10] / [11] dynamic LDS bytes of launches 1 / 2 (0: not
+ *          enqueued), [12] floats of +inf apron left of a row.  Per-layer arrays follow the
+ *          out[6] header words: m_l at [out[6] + l], the number of computed 64-bucket chunks of
+ *          layer l at [out[6] + L + l], the largest usable shift of layer l at
+ *          [out[6] + (2 + out[7]) L + l]
  *   out[2] byte offset of int32 t*[K] (reduced time t* - M, or -1 if infeasible)
  *   out[3] byte offset of the record
  *   out[4] record pitch in elements (buckets per row, a multiple of 64)
  *   out[5] record rows per candidate (L: row l holds layer l)
+ *   out[6] int32 words of the header before its per-layer arrays
+ *   out[7] int32 words per layer of the wave plan that sits between the second and the last
+ *          per-layer array
  * Element (k, l, t') of the record is at out[3] + ((k * out[5] + l) * out[4] + t') * elemsize.
  * Returns SPDY_DP_OK or a size / workspace error. */
-int spdy_dp_workspace_layout(int K, int L, int S, int B, size_t workspace_bytes, size_t out[6]);
+int spdy_dp_workspace_layout(int K, int L, int S, int B, size_t workspace_bytes, size_t out[8]);
 
 /* Static, human-readable text for a status code. */
 const char *spdy_dp_strerror(int status);

@@ -85,12 +85,12 @@ def spdy_dp_workspace_bytes_min(K: int, L: int, S: int, B: int) -> int:
 def spdy_dp_workspace_layout(K: int, L: int, S: int, B: int, workspace_bytes: int) -> dict:
     """Where things are in a workspace of that size (see the header): variant (0 = fp32 D
     record, 1 = one-byte level record), byte offsets, record pitch and rows per candidate."""
-    out = (ctypes.c_size_t * 6)()
+    out = (ctypes.c_size_t * 8)()
     st = lib().spdy_dp_workspace_layout(K, L, S, B, int(workspace_bytes), out)
     if st != OK:
         raise SpdyDpError(st)
     keys = ("variant", "meta_offset", "tstar_offset", "record_offset", "record_pitch",
-            "record_rows")
+            "record_rows", "header_words", "plan_words")
     return dict(zip(keys, (int(v) for v in out)))
 
 
@@ -119,9 +119,30 @@ def alloc_workspace(K: int, L: int, S: int, B: int, device=None, compact: bool =
     """Workspace tensor: the fast fp32-record size, or the 4x smaller level-record size."""
     n = (spdy_dp_workspace_bytes_min if compact else spdy_dp_workspace_bytes)(K, L, S, B)
     if n == 0:
-        raise SpdyDpError(lib().spdy_dp_workspace_layout(K, L, S, B, 2 ** 62,
-                                                         (ctypes.c_size_t * 6)()))
+        raise _size_error(K, L, S, B)
     return torch.empty(n, dtype=torch.uint8, device=device or "cuda")
+
+
+def _size_error(K: int, L: int, S: int, B: int) -> "SpdyDpError":
+    return SpdyDpError(lib().spdy_dp_workspace_layout(K, L, S, B, 2 ** 62,
+                                                      (ctypes.c_size_t * 8)()))
+
+
+def _own_workspace(n: int, device, stream):
+    """A workspace the wrapper allocates itself and drops when it returns, while the kernels that
+    use it are still queued on ``stream``: the caching allocator is told about that stream, so
+    it does not hand the block to other work before those kernels are done."""
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    if stream is not None:
+        ws.record_stream(stream)
+    return ws
+
+
+def _own_full_workspace(K: int, L: int, S: int, B: int, device, stream):
+    n = spdy_dp_workspace_bytes(K, L, S, B)
+    if n == 0:
+        raise _size_error(K, L, S, B)
+    return _own_workspace(n, device, stream)
 
 
 def spdy_dp_solve_batched(tau, err, B: int, profile=None, cost=None, workspace=None, stream=None):
@@ -135,7 +156,7 @@ def spdy_dp_solve_batched(tau, err, B: int, profile=None, cost=None, workspace=N
     if cost is None:
         cost = torch.empty((K,), dtype=torch.float32, device=err.device)
     if workspace is None:
-        workspace = alloc_workspace(K, L, S, B, err.device)
+        workspace = _own_full_workspace(K, L, S, B, err.device, stream)
     _dev(profile, torch.int16, "profile")
     _dev(cost, torch.float32, "cost")
     _dev(workspace, torch.uint8, "workspace")
@@ -162,7 +183,7 @@ def spdy_dp_solve_sensitivities(tau, c, w, B: int, profile=None, cost=None, work
     if cost is None:
         cost = torch.empty((K,), dtype=torch.float32, device=c.device)
     if workspace is None:
-        workspace = alloc_workspace(K, L, S, B, c.device)
+        workspace = _own_full_workspace(K, L, S, B, c.device, stream)
     _dev(profile, torch.int16, "profile")
     _dev(cost, torch.float32, "cost")
     _dev(workspace, torch.uint8, "workspace")
@@ -192,7 +213,7 @@ def spdy_dp_solve_budgets(tau, err, budgets, profile=None, cost=None, workspace=
     if cost is None:
         cost = torch.empty((J, K), dtype=torch.float32, device=err.device)
     if workspace is None:
-        workspace = alloc_workspace(K, L, S, max(budgets), err.device)
+        workspace = _own_full_workspace(K, L, S, max(budgets), err.device, stream)
     _dev(profile, torch.int16, "profile")
     _dev(cost, torch.float32, "cost")
     _dev(workspace, torch.uint8, "workspace")
@@ -219,7 +240,7 @@ def spdy_dp_solve_from_incumbent(tau, err, first_layer, B: int, incumbent_worksp
     if cost is None:
         cost = torch.empty((K,), dtype=torch.float32, device=err.device)
     if workspace is None:
-        workspace = alloc_workspace(K, L, S, B, err.device)
+        workspace = _own_full_workspace(K, L, S, B, err.device, stream)
     _dev(profile, torch.int16, "profile")
     _dev(cost, torch.float32, "cost")
     _dev(workspace, torch.uint8, "workspace")
@@ -251,7 +272,7 @@ def spdy_dp_solve_checkpointed(tau, err, B: int, stride: int = 0, profile=None, 
         if n == 0:
             raise SpdyDpError(lib().spdy_dp_solve_checkpointed(None, None, K, L, S, int(B), stride,
                                                                None, None, None, 0, None))
-        workspace = torch.empty(n, dtype=torch.uint8, device=err.device)
+        workspace = _own_workspace(n, err.device, stream)
     _dev(profile, torch.int16, "profile")
     _dev(cost, torch.float32, "cost")
     _dev(workspace, torch.uint8, "workspace")

@@ -35,6 +35,8 @@
 
 #include <stdint.h>
 
+#include <mutex>
+
 #include "spdy_dp.h"
 
 namespace {
@@ -77,7 +79,7 @@ static_assert(kInPlaceFits, "path 1 must be exactly the in-place case");
 constexpr int kBatch = 8;                 // level tables are padded to a multiple of this
 constexpr unsigned kNoLevel = 0xFF;
 constexpr size_t kAlign = 256;
-constexpr int kMetaHeader = 8;       // int32 words before the per-layer arrays
+constexpr int kMetaHeader = 16;      // int32 words before the per-layer arrays
 // meta: header | m_l [L] | chunks of row l [L] | chunk boundaries of the team waves [L][stride]
 //       | largest usable shift of layer l [L]
 constexpr int kRangeStride = kMaxFillWaves + 1;
@@ -89,7 +91,13 @@ constexpr int kRangeStride = kMaxFillWaves + 1;
 enum MetaWord {
     kMetaBudget = 0, kMetaMinTime = 1, kMetaRow = 2, kMetaPath = 3, kMetaTeamWaves = 4,
     kMetaTeams = 5, kMetaInPlace = 6,
-    kMetaStage = 7      // bytes of LDS the global-row launch has for the windows of its tiles
+    kMetaStage = 7,     // bytes of LDS the global-row launch has for the windows of its tiles
+    // what the choice of the path was made from (read back by tests, not by the kernels)
+    kMetaWaves = 8,     // waves of a fill workgroup
+    kMetaMaxGroup = 9,  // most chunks a wave keeps in registers
+    kMetaLdsSmall = 10, // dynamic LDS bytes of the in-place launch
+    kMetaLdsLarge = 11, // dynamic LDS bytes of the two-row launch (0: not enqueued)
+    kMetaHalo = 12      // floats of the +inf apron left of a row
 };
 
 enum Variant { kValueRecord = 0, kLevelRecord = 1 };
@@ -273,6 +281,11 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots
         meta[kMetaTeamWaves] = waves / teams;
         meta[kMetaInPlace] = inplace;
         meta[kMetaStage] = lds_stage;
+        meta[kMetaWaves] = waves;
+        meta[kMetaMaxGroup] = max_group;
+        meta[kMetaLdsSmall] = lds_small;
+        meta[kMetaLdsLarge] = lds_large;
+        meta[kMetaHalo] = kHalo;
         s_budget = bp;
         s_team_waves = waves / teams;
     }
@@ -1375,6 +1388,35 @@ int launch_status()
     return hipGetLastError() == hipSuccess ? SPDY_DP_OK : SPDY_DP_ERR_LAUNCH;
 }
 
+// What the host keeps per device between calls: the number of compute units (asked once, not per
+// solve).
+constexpr int kMaxDevices = 64;
+struct DeviceState {
+    int units = 0;
+};
+std::mutex g_device_lock;
+DeviceState g_device[kMaxDevices];
+
+// The current device's state.  Returns SPDY_DP_OK or SPDY_DP_ERR_LAUNCH (the runtime refused a
+// query).
+int device_state(DeviceState *out)
+{
+    int device = 0;
+    if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices)
+        return SPDY_DP_ERR_LAUNCH;
+    std::lock_guard<std::mutex> hold(g_device_lock);
+    DeviceState &st = g_device[device];
+    if (st.units <= 0) {
+        int units = 0;
+        if (hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) !=
+                hipSuccess || units <= 0)
+            return SPDY_DP_ERR_LAUNCH;
+        st.units = units;
+    }
+    *out = st;
+    return SPDY_DP_OK;
+}
+
 template <bool kLevel, bool kNarrow, bool kBlocks = false>
 int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume resume, int K, int L,
                 int S, int B, char *ws, float *cost, hipStream_t q, Blocks blocks = Blocks{})
@@ -1400,11 +1442,10 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     // updated in place whatever the reduced length turns out to be, so one row bounds the need;
     // otherwise two rows alternate.
     // workgroups the chip holds at once: two per compute unit for either variant
-    int device = 0, units = 0;
-    if (hipGetDevice(&device) != hipSuccess ||
-        hipDeviceGetAttribute(&units, hipDeviceAttributeMultiprocessorCount, device) != hipSuccess ||
-        units <= 0)
+    DeviceState dev;
+    if (device_state(&dev) != SPDY_DP_OK)
         return SPDY_DP_ERR_LAUNCH;
+    const int units = dev.units;
     // Workgroups that take turns at the priority pay off when a launch is one or two rounds of
     // workgroups (measured: K = 4 x units 4 % faster, 16 x units no gain and a slightly slower
     // kernel), and need pairs of workgroups to begin with.
@@ -1684,7 +1725,7 @@ size_t spdy_dp_workspace_bytes_min(int K, int L, int S, int B)
     return lay.status == SPDY_DP_OK ? lay.total_level : 0;
 }
 
-int spdy_dp_workspace_layout(int K, int L, int S, int B, size_t workspace_bytes, size_t out[6])
+int spdy_dp_workspace_layout(int K, int L, int S, int B, size_t workspace_bytes, size_t out[8])
 {
     if (!out)
         return SPDY_DP_ERR_NULL;
@@ -1697,6 +1738,8 @@ int spdy_dp_workspace_layout(int K, int L, int S, int B, size_t workspace_bytes,
     out[3] = lay.record_off;
     out[4] = lay.row;
     out[5] = (size_t)L;
+    out[6] = (size_t)kMetaHeader;
+    out[7] = (size_t)kRangeStride;
     return SPDY_DP_OK;
 }
 

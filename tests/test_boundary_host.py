@@ -37,7 +37,7 @@ def test_library_exports_every_declared_function(binding):
 
 def test_status_codes_match_header(binding):
     text = open(HEADER).read()
-    codes = dict(re.findall(r"#define\s+SPDY_DP_(\w+)\s+\(?(-?\d+)\)?", text))
+    codes = dict(re.findall(r"#define\s+SPDY_DP_(OK|ERR_\w+)\s+\(?(-?\d+)\)?", text))
     assert int(codes["OK"]) == binding.OK
     assert int(codes["ERR_NULL"]) == binding.ERR_NULL
     assert int(codes["ERR_DIM"]) == binding.ERR_DIM

@@ -63,7 +63,9 @@ def check_tables(dp, tau, err_k, B, ws, k, K):
     L, S = tau.shape
     D, P, prof, cost = oracle.tables_ref(tau, err_k, B)
     lay = dp.spdy_dp_workspace_layout(K, L, S, B, ws.numel())
-    meta = ws[lay["meta_offset"]:lay["meta_offset"] + 4 * (8 + 20 * L)].cpu().numpy().view(np.int32)
+    H, plan = lay["header_words"], lay["plan_words"]
+    meta = ws[lay["meta_offset"]:lay["meta_offset"] + 4 * (H + (3 + plan) * L)].cpu().numpy() \
+        .view(np.int32)
     mn = tau.min(axis=1).astype(np.int64)
     M = int(mn.sum())
     tstar = ws[lay["tstar_offset"] + 4 * k:lay["tstar_offset"] + 4 * k + 4].cpu().numpy() \
@@ -73,27 +75,41 @@ def check_tables(dp, tau, err_k, B, ws, k, K):
         return
     bp = B - M
     assert meta[0] == bp and meta[1] == M and meta[2] == (bp + 64) // 64 * 64
-    assert (meta[8:8 + L] == mn).all()
-    nact = meta[8 + L:8 + 2 * L].astype(np.int64)
+    assert (meta[H:H + L] == mn).all()
+    nact = meta[H + L:H + 2 * L].astype(np.int64)
     # the largest usable shift of each layer (what a staged tile of the global-row path reaches)
     delta = tau.astype(np.int64) - mn[:, None]
-    assert (meta[8 + 19 * L:8 + 20 * L] == np.where(delta <= bp, delta, 0).max(axis=1)).all()
+    assert (meta[H + (2 + plan) * L:H + (3 + plan) * L] ==
+            np.where(delta <= bp, delta, 0).max(axis=1)).all()
     lo = np.cumsum(mn)
     pitch, rows = lay["record_pitch"], lay["record_rows"]
     esize = 4 if lay["variant"] == 0 else 1
     a = lay["record_offset"] + k * rows * pitch * esize
     rec = ws[a:a + rows * pitch * esize].cpu().numpy()
     rec = rec.view(np.float32 if esize == 4 else np.uint8).reshape(rows, pitch)
-    if meta[3] == 0:     # rows in global memory: the reduced rows (plus aprons) exceed LDS
-        assert 2 * (meta[2] + 1792) * 4 > 160 * 1024 - 8448   # apron 28 * 64, static LDS 8448
-    # the launch with the small LDS allocation is exactly the one that updates a row in place:
-    # the row fits the registers of a workgroup's waves: 8 x 26 chunks (8 x 28 in batches of up
-    # to four candidates per compute unit, 256 units on this chip), or 16 x 10 with levels
-    per_wave = 28 if 256 < K <= 1024 else 26
-    fits = meta[2] // 64 <= (8 * per_wave if lay["variant"] == 0 else 16 * 10)
-    assert (meta[3] == 1) == bool(meta[6]) == bool(fits)
-    if meta[3] == 2:
-        assert 2 * (meta[2] + 1792) * 4 <= 160 * 1024 - 8448
+    # Which launch did the work must follow from what the header says the choice was made from
+    # (no tuning constant is repeated here): a row is updated in place exactly when the waves of
+    # a workgroup can hold all its chunks in registers; otherwise two rows (with their aprons)
+    # alternate in LDS if the larger launch has room for them, else they live in global memory.
+    path, team_waves, teams, inplace = (int(x) for x in meta[3:7])
+    waves, max_group, lds_small, lds_large, halo = (int(x) for x in meta[8:13])
+    chunks = int(meta[2]) // 64
+    row_bytes = (int(meta[2]) + halo) * 4
+    assert inplace == int(chunks <= waves * max_group)
+    if inplace:
+        assert path == 1 and row_bytes * teams <= lds_small
+        assert 1 <= teams and teams * team_waves <= waves
+        assert chunks <= team_waves * max_group         # a team's waves hold the whole row
+    elif 2 * row_bytes <= lds_large:
+        assert path == 2 and teams == 1
+    else:
+        assert path == 0 and teams == 1
+    # every wave's share of every row fits its registers when the row is updated in place
+    plan_rows = meta[H + 2 * L:H + (2 + plan) * L].reshape(L, plan)[:, :team_waves + 1]
+    assert (plan_rows[:, 0] == 0).all() and (plan_rows[:, team_waves] == nact).all()
+    assert (np.diff(plan_rows, axis=1) >= 0).all()
+    if inplace:
+        assert (np.diff(plan_rows, axis=1) <= max_group).all()
     for l in range(L):
         n = int(min(nact[l] * 64, bp + 1))
         want_D = D[l, lo[l]:lo[l] + n]
@@ -512,6 +528,69 @@ def test_a_solve_captured_in_a_graph_replays_correctly(dp):
         torch.cuda.synchronize()
         assert_same(profile.cpu().numpy(), cost.cpu().numpy(), *want, f"replay {rep}")
         assert_same(eager_p.cpu().numpy(), eager_c.cpu().numpy(), *want, f"eager {rep}")
+
+
+def test_a_solve_that_needs_the_larger_lds_launch_replays_from_a_graph(dp):
+    """Rows too long to be updated in place take the launch with the larger LDS allocation, whose
+    attribute is set by the call itself; that call, captured, must replay correctly too."""
+    dev = torch.device("cuda:0")
+    rng = np.random.default_rng(607)
+    K, L, S, B = 3, 6, 10, 17000
+    tau, err, _ = workloads.random_instance(rng, K, L, S, B, tau_max=B // 3, integer_err=3)
+    other = workloads.random_instance(rng, K, L, S, B, tau_max=B // 3)[1]
+    p_ref, c_ref = oracle.solve_ref(tau, err, B)
+    p_other, c_other = oracle.solve_ref(tau, other, B)
+    tau_d = torch.from_numpy(tau).to(dev)
+    err_d = torch.from_numpy(err).to(dev)
+    ws = dp.alloc_workspace(K, L, S, B, dev)
+    profile = torch.empty((K, L), dtype=torch.int16, device=dev)
+    cost = torch.empty((K,), dtype=torch.float32, device=dev)
+    dp.spdy_dp_solve_batched(tau_d, err_d, B, profile, cost, ws)
+    torch.cuda.synchronize()
+    lay = dp.spdy_dp_workspace_layout(K, L, S, B, ws.numel())
+    path = int(ws[lay["meta_offset"] + 12:lay["meta_offset"] + 16].cpu().numpy().view(np.int32)[0])
+    assert path == 2, "this shape is meant to take the two-row launch"
+    assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, "eager")
+    graph = torch.cuda.CUDAGraph()
+    stream = torch.cuda.Stream()
+    with torch.cuda.stream(stream):
+        with torch.cuda.graph(graph, stream=stream):
+            dp.spdy_dp_solve_batched(tau_d, err_d, B, profile, cost, ws)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        table, want = (err, (p_ref, c_ref)) if rep % 2 == 0 else (other, (p_other, c_other))
+        err_d.copy_(torch.from_numpy(table).to(dev))
+        profile.fill_(-9)
+        cost.fill_(-9.0)
+        eager_p, eager_c = dp.spdy_dp_solve_batched(tau_d, err_d, B)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert_same(profile.cpu().numpy(), cost.cpu().numpy(), *want, f"replay {rep}")
+        assert_same(eager_p.cpu().numpy(), eager_c.cpu().numpy(), *want, f"eager {rep}")
+
+
+def test_a_side_stream_with_the_wrappers_own_workspace(dp):
+    """With no workspace given the wrapper allocates one and drops it on return, while the kernels
+    are still queued on the caller's stream; allocations made right after on another stream must
+    not get that block before the solve is done."""
+    dev = torch.device("cuda:0")
+    tau, err, B = workloads.generate(workloads.CONFIGS["rn50_k1"], K=24)
+    p_ref, c_ref = oracle.solve_ref(tau, err, B, threads=CPU_THREADS)
+    tau_d, err_d = torch.from_numpy(tau).to(dev), torch.from_numpy(err).to(dev)
+    K, L, S = err.shape
+    n = dp.spdy_dp_workspace_bytes(K, L, S, B)
+    side = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for rep in range(3):
+        side.wait_stream(torch.cuda.current_stream())
+        profile, cost = dp.spdy_dp_solve_batched(tau_d, err_d, B, stream=side)
+        # same-sized blocks on the current stream, scribbled over at once
+        junk = [torch.empty(n, dtype=torch.uint8, device=dev).fill_(0x77) for _ in range(2)]
+        side.synchronize()
+        torch.cuda.synchronize()
+        assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, f"rep {rep}")
+        del junk
 
 
 def test_two_host_threads_on_their_own_streams(dp):
