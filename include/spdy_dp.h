@@ -77,6 +77,12 @@ extern "C" {
                                       hipGetLastError); unlike the argument errors above it can
                                       come back after earlier kernels of the call were enqueued,
                                       so the outputs are then undefined                          */
+#define SPDY_DP_ERR_STATIC_LIMIT (-10) /* spdy_dp_solve_batched_static: the problem needs more
+                                      than SPDY_DP_STATIC_WORKSPACE_BYTES of workspace           */
+
+/* Size of the workspace built into the library for spdy_dp_solve_batched_static (64 MiB of
+ * device memory per GPU the library runs on, held until the process ends). */
+#define SPDY_DP_STATIC_WORKSPACE_BYTES ((size_t)64 << 20)
 
 /* Bytes of device workspace for the fast variant (fp32 D recorded per cell), or 0 if the sizes
  * are invalid.  About 4 * K * L * (B + 1) bytes, plus 8 * K * (B + 1) when two rows of B + 1 floats
@@ -97,6 +103,21 @@ size_t spdy_dp_workspace_bytes_min(int K, int L, int S, int B);
 int spdy_dp_solve_batched(const int32_t *tau, const float *err, int K, int L, int S, int B,
                           int16_t *profile, float *cost, void *workspace, size_t workspace_bytes,
                           void *stream);
+
+/* spdy_dp_solve_batched for callers that cannot allocate device memory or be handed a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The
+ * workspace is a fixed array of SPDY_DP_STATIC_WORKSPACE_BYTES inside the library's code object
+ * (one copy per GPU); this call allocates nothing, frees nothing and calls no allocating routine.
+ * Arguments, outputs and results are those of spdy_dp_solve_batched; the D record is used when
+ * spdy_dp_workspace_bytes(K, L, S, B) fits the array, the level record when only
+ * spdy_dp_workspace_bytes_min does, and SPDY_DP_ERR_STATIC_LIMIT is returned (nothing enqueued)
+ * when neither does (one ResNet-50-sized table, L = 54, S = 40, B = 10^4, takes 2.2 MB with the
+ * D record: 30 such candidates fit, 123 with the level record).
+ * Every call on a GPU uses that GPU's one array, whatever the stream: calls that overlap in time
+ * on one GPU race and return garbage; order them on one stream or with events.  Nothing needs
+ * clearing between calls (no kernel assumes anything about the array's contents). */
+int spdy_dp_solve_batched_static(const int32_t *tau, const float *err, int K, int L, int S, int B,
+                                 int16_t *profile, float *cost, void *stream);
 
 /* First part of Alg. 1: fills the tables layer by layer (Eq. 2-3), records D or the chosen level
  * of every computed cell in the workspace, and takes the final argmin over t <= B.  Writes

@@ -16,8 +16,11 @@ _lib = None
 
 OK = 0
 ERR_NULL, ERR_DIM, ERR_LEVELS, ERR_WORKSPACE, ERR_OVERFLOW, ERR_LAUNCH = -1, -2, -3, -4, -5, -9
+ERR_STATIC_LIMIT = -10
+STATIC_WORKSPACE_BYTES = 64 << 20     # SPDY_DP_STATIC_WORKSPACE_BYTES in the header
 
 EXPORTS = ("spdy_dp_workspace_bytes", "spdy_dp_workspace_bytes_min", "spdy_dp_solve_batched",
+           "spdy_dp_solve_batched_static",
            "spdy_dp_solve_sensitivities", "spdy_dp_solve_budgets",
            "spdy_dp_solve_from_incumbent", "spdy_dp_workspace_bytes_checkpointed",
            "spdy_dp_solve_checkpointed", "spdy_dp_fill", "spdy_dp_backtrace",
@@ -46,6 +49,8 @@ def lib() -> ctypes.CDLL:
         L.spdy_dp_workspace_bytes_min.argtypes = [i, i, i, i]
         L.spdy_dp_solve_batched.restype = i
         L.spdy_dp_solve_batched.argtypes = [vp, vp, i, i, i, i, vp, vp, vp, sz, vp]
+        L.spdy_dp_solve_batched_static.restype = i
+        L.spdy_dp_solve_batched_static.argtypes = [vp, vp, i, i, i, i, vp, vp, vp]
         L.spdy_dp_solve_sensitivities.restype = i
         L.spdy_dp_solve_sensitivities.argtypes = [vp, vp, vp, i, i, i, i, vp, vp, vp, sz, vp]
         L.spdy_dp_solve_budgets.restype = i
@@ -163,6 +168,25 @@ def spdy_dp_solve_batched(tau, err, B: int, profile=None, cost=None, workspace=N
     st = lib().spdy_dp_solve_batched(tau.data_ptr(), err.data_ptr(), K, L, S, int(B),
                                      profile.data_ptr(), cost.data_ptr(), workspace.data_ptr(),
                                      workspace.numel(), _stream(stream))
+    if st != OK:
+        raise SpdyDpError(st)
+    return profile, cost
+
+
+def spdy_dp_solve_batched_static(tau, err, B: int, profile=None, cost=None, stream=None):
+    """``spdy_dp_solve_batched`` on the workspace built into the library (no allocation inside the
+    call when ``profile`` and ``cost`` are given).  Calls that overlap on one GPU race."""
+    tau = _dev(tau, torch.int32, "tau")
+    err = _dev(err, torch.float32, "err")
+    K, L, S = _shapes(tau, err)
+    if profile is None:
+        profile = torch.empty((K, L), dtype=torch.int16, device=err.device)
+    if cost is None:
+        cost = torch.empty((K,), dtype=torch.float32, device=err.device)
+    _dev(profile, torch.int16, "profile")
+    _dev(cost, torch.float32, "cost")
+    st = lib().spdy_dp_solve_batched_static(tau.data_ptr(), err.data_ptr(), K, L, S, int(B),
+                                            profile.data_ptr(), cost.data_ptr(), _stream(stream))
     if st != OK:
         raise SpdyDpError(st)
     return profile, cost

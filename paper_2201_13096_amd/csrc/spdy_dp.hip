@@ -39,6 +39,11 @@
 
 #include "spdy_dp.h"
 
+// Workspace of spdy_dp_solve_batched_static: device memory that belongs to the loaded code
+// object, so the entry point never allocates.  In host code this name is only a handle for
+// hipGetSymbolAddress; the address the kernels get is looked up once per device.
+static __device__ __align__(256) unsigned char scratch[SPDY_DP_STATIC_WORKSPACE_BYTES];
+
 namespace {
 
 constexpr int kWave = 64;            // lanes per wavefront = buckets per chunk
@@ -1389,17 +1394,18 @@ int launch_status()
 }
 
 // What the host keeps per device between calls: the number of compute units (asked once, not per
-// solve).
+// solve) and where this device's copy of `scratch` lives.
 constexpr int kMaxDevices = 64;
 struct DeviceState {
     int units = 0;
+    void *scratch = nullptr;
 };
 std::mutex g_device_lock;
 DeviceState g_device[kMaxDevices];
 
-// The current device's state.  Returns SPDY_DP_OK or SPDY_DP_ERR_LAUNCH (the runtime refused a
-// query).
-int device_state(DeviceState *out)
+// The current device's state; `with_scratch` also resolves the device address of `scratch`.
+// Returns SPDY_DP_OK or SPDY_DP_ERR_LAUNCH (the runtime refused a query).
+int device_state(bool with_scratch, DeviceState *out)
 {
     int device = 0;
     if (hipGetDevice(&device) != hipSuccess || device < 0 || device >= kMaxDevices)
@@ -1412,6 +1418,12 @@ int device_state(DeviceState *out)
                 hipSuccess || units <= 0)
             return SPDY_DP_ERR_LAUNCH;
         st.units = units;
+    }
+    if (with_scratch && !st.scratch) {
+        void *ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr)
+            return SPDY_DP_ERR_LAUNCH;
+        st.scratch = ptr;
     }
     *out = st;
     return SPDY_DP_OK;
@@ -1443,7 +1455,7 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     // otherwise two rows alternate.
     // workgroups the chip holds at once: two per compute unit for either variant
     DeviceState dev;
-    if (device_state(&dev) != SPDY_DP_OK)
+    if (device_state(false, &dev) != SPDY_DP_OK)
         return SPDY_DP_ERR_LAUNCH;
     const int units = dev.units;
     // Workgroups that take turns at the priority pay off when a launch is one or two rounds of
@@ -1772,6 +1784,25 @@ int spdy_dp_solve_batched(const int32_t *tau, const float *err, int K, int L, in
                       workspace_bytes, stream);
 }
 
+int spdy_dp_solve_batched_static(const int32_t *tau, const float *err, int K, int L, int S, int B,
+                                 int16_t *profile, float *cost, void *stream)
+{
+    if (!tau || !err || !profile || !cost)
+        return SPDY_DP_ERR_NULL;
+    // sizes first: nothing is looked up or enqueued for a problem that does not fit
+    const Layout lay = make_layout(K, L, S, B, SPDY_DP_STATIC_WORKSPACE_BYTES);
+    if (lay.status == SPDY_DP_ERR_WORKSPACE)
+        return SPDY_DP_ERR_STATIC_LIMIT;
+    if (lay.status != SPDY_DP_OK)
+        return lay.status;
+    DeviceState dev;
+    const int st = device_state(true, &dev);
+    if (st != SPDY_DP_OK)
+        return st;
+    return solve_impl(tau, ErrSource{err, nullptr, nullptr}, K, L, S, B, profile, cost,
+                      dev.scratch, SPDY_DP_STATIC_WORKSPACE_BYTES, stream);
+}
+
 int spdy_dp_solve_sensitivities(const int32_t *tau, const float *c, const float *w, int K, int L,
                                 int S, int B, int16_t *profile, float *cost, void *workspace,
                                 size_t workspace_bytes, void *stream)
@@ -1833,6 +1864,8 @@ const char *spdy_dp_strerror(int status)
     case SPDY_DP_ERR_WORKSPACE: return "workspace smaller than spdy_dp_workspace_bytes_min()";
     case SPDY_DP_ERR_OVERFLOW: return "problem size overflows the index arithmetic";
     case SPDY_DP_ERR_LAUNCH: return "HIP runtime refused a kernel launch";
+    case SPDY_DP_ERR_STATIC_LIMIT:
+        return "problem needs more than the built-in workspace of spdy_dp_solve_batched_static";
     default: return "unknown status";
     }
 }

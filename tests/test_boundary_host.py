@@ -45,6 +45,10 @@ def test_status_codes_match_header(binding):
     assert int(codes["ERR_WORKSPACE"]) == binding.ERR_WORKSPACE
     assert int(codes["ERR_OVERFLOW"]) == binding.ERR_OVERFLOW
     assert int(codes["ERR_LAUNCH"]) == binding.ERR_LAUNCH
+    assert int(codes["ERR_STATIC_LIMIT"]) == binding.ERR_STATIC_LIMIT
+    limit = re.search(r"#define\s+SPDY_DP_STATIC_WORKSPACE_BYTES\s+\(\(size_t\)(\d+)\s*<<\s*(\d+)\)",
+                      text)
+    assert int(limit.group(1)) << int(limit.group(2)) == binding.STATIC_WORKSPACE_BYTES
     for v in codes.values():
         assert binding.spdy_dp_strerror(int(v)) != "unknown status"
     assert binding.spdy_dp_strerror(-1234) == "unknown status"
@@ -113,6 +117,20 @@ def test_argument_errors_are_reported_before_any_launch(binding):
     assert solve(fake, fake, 1, 1, 1, 1, fake, fake, fake, 8, None) == binding.ERR_WORKSPACE
     assert solve(fake, fake, 2 ** 31 - 1, 2 ** 31 - 1, 2, 2 ** 31 - 2000, fake, fake, fake,
                  1 << 20, None) == binding.ERR_OVERFLOW
+    # the entry point with the built-in workspace: sizes are checked before the device is touched
+    static = lib.spdy_dp_solve_batched_static
+    assert static(None, fake, 1, 1, 1, 1, fake, fake, None) == binding.ERR_NULL
+    assert static(fake, None, 1, 1, 1, 1, fake, fake, None) == binding.ERR_NULL
+    assert static(fake, fake, 1, 1, 1, 1, None, fake, None) == binding.ERR_NULL
+    assert static(fake, fake, 1, 1, 1, 1, fake, None, None) == binding.ERR_NULL
+    assert static(fake, fake, 0, 1, 1, 1, fake, fake, None) == binding.ERR_DIM
+    assert static(fake, fake, 1, 1, 300, 1, fake, fake, None) == binding.ERR_LEVELS
+    assert binding.spdy_dp_workspace_bytes_min(123, 54, 40, 10000) <= \
+        binding.STATIC_WORKSPACE_BYTES < binding.spdy_dp_workspace_bytes_min(124, 54, 40, 10000)
+    assert static(fake, fake, 124, 54, 40, 10000, fake, fake, None) == binding.ERR_STATIC_LIMIT
+    assert static(fake, fake, 1024, 54, 40, 10000, fake, fake, None) == binding.ERR_STATIC_LIMIT
+    assert static(fake, fake, 2 ** 31 - 1, 2 ** 31 - 1, 2, 2 ** 31 - 2000, fake, fake, None) == \
+        binding.ERR_OVERFLOW
     one = (ctypes.c_int32 * 2)(5, 9)
     neg = (ctypes.c_int32 * 2)(5, -1)
     multi = lib.spdy_dp_solve_budgets
