@@ -19,21 +19,69 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# Plain (non-packed) vector ALU peak of the chip: 256 compute units x 4 SIMDs x 16 lanes, one
-# 32-bit lane-operation per lane per clock at 2.4 GHz.  (The published 157.3 TFLOP/s fp32 vector
-# figure is this number x 2 for fused multiply-add x 2 for packed fp32; neither applies to an
-# add / compare / select chain.)
-ALU_PEAK_LANE_OPS = 256 * 64 * 2.4e9
-# One update of Alg. 1's inner loop: an fp32 add and an fp32 min when D itself is recorded;
-# an fp32 add, a compare and two selects (value, level) when the level is tracked per cell.
-LANE_OPS_PER_UPDATE = {"d": 2, "level": 4}
-# LDS: one 4-byte read of the shifted previous row per update; 128 bytes per clock per compute
-# unit for 32-bit reads (64 lanes in two clocks).
-LDS_PEAK_BYTES = 256 * 128 * 2.4e9
-LDS_BYTES_PER_UPDATE = 4
-# HBM bytes per launch of the fill kernel, from FETCH_SIZE / WRITE_SIZE counter runs scaled by a
-# plain copy of known size (profiles/dp_fill_rn50_k1024_*.md).  None where not measured.
-MEASURED_TRAFFIC_BYTES = {("rn50_k1024", "d"): 957e6, ("rn50_k1024", "level"): 246e6}
+# Nominal peaks of the chip (256 compute units, 2.4 GHz).
+# LDS: 128 bytes per clock per compute unit for reads of up to 64 bits per lane (a 64-lane 32-bit
+# read takes two clocks); aligned 128-bit reads run at twice that on this generation.
+# Vector ALU: 128 plain 32-bit lane-instructions per clock per compute unit (4 SIMDs, a 64-lane
+# instruction every two clocks each).  The published 157.3 TFLOP/s fp32 vector figure is this
+# x 2 for fused multiply-add; an add / min chain gets one operation per instruction.  (The rate
+# probe issues 98 - 105 lane-instructions per clock per compute unit on add / min / min3 mixes,
+# counted with SQ_INSTS_VALU, so the unit is not a 64-lane one.)
+COMPUTE_UNITS = 256
+CLOCK_HZ = 2.4e9
+LDS_PEAK_B32 = COMPUTE_UNITS * 128 * CLOCK_HZ
+LDS_PEAK_B128 = COMPUTE_UNITS * 256 * CLOCK_HZ
+ALU_PEAK_LANE_OPS = COMPUTE_UNITS * 128 * CLOCK_HZ
+# Algorithmic cost of one executed update of Alg. 1's inner loop.
+#   LDS: one 4-byte read of the shifted previous row plus the 4 / S bytes the new row's write
+#        costs per update.
+#   ALU, D record: an fp32 add and an fp32 min; as built one v_min3_f32 folds two updates, so 1.5
+#        issued instructions per update.  Level record: add, compare, select of the level, min.
+LANE_OPS_PER_UPDATE = {"d": 2.0, "level": 4.0}
+LANE_OPS_AS_BUILT = {"d": 1.5, "level": 4.0}
+PROFILES = os.path.join(ROOT, "profiles")
+KERNEL_SOURCE = os.path.join(ROOT, "paper_2201_13096_amd", "csrc", "spdy_dp.hip")
+PROBE = os.path.join(ROOT, "paper_2201_13096_amd", "peaks_probe")
+
+
+def kernel_source_id() -> str:
+    """Short hash of the HIP source: counter figures taken from a tracked profile only count while
+    the kernel they were taken on is the one in the tree."""
+    import hashlib
+    with open(KERNEL_SOURCE, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:12]
+
+
+def tracked_traffic(workload: str, record: str):
+    """HBM bytes per launch of the fill kernel from profiles/dp_fill_hbm_traffic.txt (FETCH_SIZE +
+    WRITE_SIZE counter runs scaled by a plain copy of known size), or None when the file has no
+    line for this workload and record taken on the present kernel source."""
+    path = os.path.join(PROFILES, "dp_fill_hbm_traffic.txt")
+    try:
+        with open(path) as f:
+            for line in f:
+                tok = line.split("#", 1)[0].split()
+                if len(tok) >= 5 and tok[0] == workload and tok[1] == record \
+                        and tok[2] == kernel_source_id():
+                    return float(tok[3]) + float(tok[4])
+    except OSError:
+        pass
+    return None
+
+
+def measured_peaks():
+    """Run the rate probe (a separate executable) as a child process; None if it is not built or
+    fails.  Called before this process touches the GPU."""
+    import subprocess
+    if not os.path.exists(PROBE):
+        return None
+    try:
+        res = subprocess.run([PROBE], capture_output=True, text=True, timeout=120)
+        if res.returncode != 0:
+            return None
+        return json.loads(res.stdout.strip().splitlines()[-1])
+    except (OSError, ValueError, subprocess.TimeoutExpired):
+        return None
 
 
 def executed_updates_per_candidate(tau: np.ndarray, B: int, merge_equal_times: bool) -> int:
@@ -93,6 +141,16 @@ def host_cpu_model() -> str:
     return "unknown"
 
 
+def host_threads() -> int:
+    """Threads the oracle leg may use: the cores this process is allowed on, at most 16 (the CPU
+    share that goes with one GPU on a shared host)."""
+    try:
+        n = len(os.sched_getaffinity(0))
+    except (AttributeError, OSError):
+        n = os.cpu_count() or 1
+    return max(1, min(16, n))
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -119,6 +177,12 @@ def main() -> int:
                     help="time spdy_dp_solve_batched as one call instead of its two stages "
                          "(no fill-stage events, so no roofline objects)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-probe", action="store_true",
+                    help="do not run the VALU / LDS rate probe before the benchmark")
+    ap.add_argument("--settle-steps", type=int, default=200,
+                    help="steps run after the timed ones and timed separately (reported as "
+                         "steady_state: the core clock only settles after some tens of "
+                         "milliseconds of load)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (a known-size reference for "
                          "FETCH_SIZE / WRITE_SIZE counter runs)")
@@ -127,6 +191,9 @@ def main() -> int:
         print("bench.py: this build runs on ONE GPU (candidates would shard across GPUs with no "
               "communication inside a solve); --gpus must be 1", file=sys.stderr)
         return 2
+
+    # the rate probe runs as a child process of its own, before this process touches the GPU
+    peaks = None if args.no_probe else measured_peaks()
 
     import torch
 
@@ -259,6 +326,26 @@ def main() -> int:
     ms_per_step = (t1 - t0) * 1e3 / args.steps
     fill_samples = [a.elapsed_time(b) for a, b in evs if a is not None]
     fill_ms = float(np.mean(fill_samples))
+    p_gpu = profile.cpu().numpy()
+    c_gpu = cost.cpu().numpy()
+
+    # the same again, after the timed region, once the clocks have settled (reported beside it)
+    steady = None
+    if args.settle_steps > 0:
+        evs2 = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+                if i % 4 == 0 else (None, None) for i in range(args.settle_steps)]
+        for _ in range(args.settle_steps // 2):
+            step()
+        torch.cuda.synchronize()
+        t2 = time.perf_counter()
+        for a, b in evs2:
+            step(a, b)
+        torch.cuda.synchronize()
+        t3 = time.perf_counter()
+        steady = {"steps": args.settle_steps,
+                  "ms_per_step": (t3 - t2) * 1e3 / args.settle_steps,
+                  "kernel_ms": float(np.mean([a.elapsed_time(b) for a, b in evs2
+                                              if a is not None]))}
 
     nominal = K * L * S * B
     if args.record == "d":
@@ -268,17 +355,64 @@ def main() -> int:
     else:                                         # more than 64 levels: every level is visited
         executed = K * executed_updates_per_candidate(tau, B, False)
     value = nominal / (ms_per_step * 1e-3)
-    ops = LANE_OPS_PER_UPDATE[args.record]
-    achieved = executed * ops / (fill_ms * 1e-3)
-    lds_achieved = executed * LDS_BYTES_PER_UPDATE / (fill_ms * 1e-3)
+    seconds = fill_ms * 1e-3
+    lds_bytes = executed * 4.0 * (1.0 + 1.0 / S)
+    lane_ops = executed * LANE_OPS_PER_UPDATE[args.record]
+    lane_ops_built = executed * LANE_OPS_AS_BUILT[args.record]
 
-    p_gpu = profile.cpu().numpy()
-    c_gpu = cost.cpu().numpy()
+    def rate(obj, key):
+        return None if peaks is None or obj not in peaks else peaks[obj].get(key)
+
+    # The D-record fill is bound by LDS reads (one 32-bit read of the shifted row per update, an
+    # add and half a v_min3 beside it); the level-record fill by the vector ALU (four instructions
+    # per update).  Both objects are always reported; `roofline` is the binding one.
+    lds_obj = {
+        "bound": "lds",
+        "kernel": "dp_fill",
+        "achieved": lds_bytes / seconds / 1e12,
+        "peak": LDS_PEAK_B32 / 1e12,
+        "unit": "TB/s",
+        "frac": lds_bytes / seconds / LDS_PEAK_B32,
+        "bytes_per_update": 4.0 * (1.0 + 1.0 / S),
+        "peak_is": "nominal: 256 CU x 128 B/clk x 2.4 GHz, reads of up to 64 bits per lane",
+        "peak_measured": rate("lds_read_b32", "tb_per_s"),
+        "frac_of_measured": None if rate("lds_read_b32", "tb_per_s") is None
+        else lds_bytes / seconds / 1e12 / rate("lds_read_b32", "tb_per_s"),
+        "peak_128bit_nominal": LDS_PEAK_B128 / 1e12,
+        "peak_128bit_measured": rate("lds_read_b128", "tb_per_s"),
+    }
+    probe_mix = "valu_add_add_min3" if args.record == "d" else "valu_add_cmp_sel_min"
+    valu_obj = {
+        "bound": "alu",
+        "kernel": "dp_fill",
+        "achieved": lane_ops / seconds / 1e12,
+        "peak": ALU_PEAK_LANE_OPS / 1e12,
+        "unit": "Tlane-op/s",
+        "frac": lane_ops / seconds / ALU_PEAK_LANE_OPS,
+        "lane_ops_per_update": LANE_OPS_PER_UPDATE[args.record],
+        "as_built": {"lane_ops_per_update": LANE_OPS_AS_BUILT[args.record],
+                     "achieved": lane_ops_built / seconds / 1e12,
+                     "frac": lane_ops_built / seconds / ALU_PEAK_LANE_OPS},
+        "peak_is": "nominal: 256 CU x 128 lane-instructions/clk x 2.4 GHz (157.3 TFLOP/s / 2)",
+        "peak_measured": rate(probe_mix, "tlane_ops_per_s"),
+        "peak_measured_mix": probe_mix,
+    }
+    roofline = dict(lds_obj if args.record == "d" else valu_obj)
+    roofline.update({
+        "kernel_ms": fill_ms,
+        "kernel_ms_median": float(np.median(fill_samples)),
+        "kernel_ms_min": float(np.min(fill_samples)),
+        "executed_updates_per_s": executed / seconds,
+        "traffic": tracked_traffic(cfg.name, args.record) if K == cfg.K else None,
+    })
+    if roofline["traffic"] is not None:           # the record stream: not the bound
+        roofline["hbm_gbps"] = roofline["traffic"] / seconds / 1e9
 
     out = {
-        "metric": "DP cell-updates/s (K*L*S*B/s)",
+        "metric": "DP cell-updates/s (nominal K*L*S*B per second of whole solve)",
         "value": value,
         "unit": "cell-updates/s",
+        "executed_updates_per_s": executed / (ms_per_step * 1e-3),
         "candidates_per_s": K / (ms_per_step * 1e-3),
         "n_gpus": 1,
         "steps": args.steps,
@@ -292,40 +426,22 @@ def main() -> int:
         "config": {"workload": cfg.name + ("+overlap" if args.overlap else ""),
                    "K": K, "L": L, "S": S, "B": B, "record": args.record,
                    "executed_updates": executed, "nominal_updates": nominal},
-        "roofline": {
-            "bound": "alu",
-            "kernel": "dp_fill",
-            "achieved": achieved / 1e12,
-            "peak": ALU_PEAK_LANE_OPS / 1e12,
-            "unit": "Tlane-op/s",
-            "frac": achieved / ALU_PEAK_LANE_OPS,
-            "lane_ops_per_update": ops,
-            "kernel_ms": fill_ms,
-            "kernel_ms_median": float(np.median(fill_samples)),
-            "kernel_ms_min": float(np.min(fill_samples)),
-            "traffic": MEASURED_TRAFFIC_BYTES.get((cfg.name, args.record))
-            if K == cfg.K else None,
-        },
-        "roofline_lds": {
-            "achieved": lds_achieved / 1e12,
-            "peak": LDS_PEAK_BYTES / 1e12,
-            "unit": "TB/s",
-            "frac": lds_achieved / LDS_PEAK_BYTES,
-        },
+        "roofline": roofline,
+        "roofline_lds": lds_obj,
+        "roofline_valu": valu_obj,
+        "steady_state": steady,
+        "measured_peaks": peaks,
     }
-
-    if out["roofline"]["traffic"] is not None:    # the record stream, not the bound
-        out["roofline"]["hbm_gbps"] = out["roofline"]["traffic"] / (fill_ms * 1e-3) / 1e9
-
     if not args.no_cpu_baseline:
         import oracle
-        threads = min(16, os.cpu_count() or 1)
-        # bounded sample: as many candidates of this workload as about 20 s of CPU work allows
+        threads = host_threads()
+        # (i) one thread on min(K, 8) candidates; (ii) all threads on a bounded sample: as many
+        # candidates of this workload as about 20 s of CPU work allows
+        n1 = min(K, 8)
         t_one0 = time.perf_counter()
-        oracle.solve_ref(tau, err[:1], B)
-        t_one = time.perf_counter() - t_one0
-        n = int(max(threads, min(K, 20.0 / max(t_one, 1e-6))))
-        n = min(K, n)
+        oracle.solve_ref(tau, err[:n1], B)
+        t_one = (time.perf_counter() - t_one0) / n1
+        n = int(min(K, max(threads, 20.0 * threads / max(t_one, 1e-6))))
         t_c0 = time.perf_counter()
         p_ref, c_ref = oracle.solve_ref(tau, err[:n], B, threads=threads)
         t_c = time.perf_counter() - t_c0
@@ -334,29 +450,36 @@ def main() -> int:
             "unit": "cell-updates/s",
             "cores": threads,
             "kind": "oracle",
-            "sample": f"first {n} of {K} candidates of {cfg.name}, {threads} threads; "
-                      f"one candidate on one thread took {t_one * 1e3:.1f} ms",
-            "single_thread_ms_per_candidate": t_one * 1e3,
+            "sample": f"first {n} of {K} candidates of {cfg.name} on {threads} threads "
+                      f"({t_c:.2f} s); single thread: first {n1} candidates, "
+                      f"{t_one * 1e3:.1f} ms per candidate",
+            "candidates_per_s": n / t_c,
+            "single_thread": {"candidates": n1, "ms_per_candidate": t_one * 1e3,
+                              "value": L * S * B / t_one},
             "cpu": host_cpu_model(),
+            "host_logical_cores": os.cpu_count(),
         }
         out["parity"] = bool((p_gpu[:n] == p_ref).all() and
                              (c_gpu[:n].view(np.uint32) == c_ref.view(np.uint32)).all())
     if args.checkpoints is not None:
-        del out["roofline"], out["roofline_lds"]
+        for key in ("roofline", "roofline_lds", "roofline_valu"):
+            out.pop(key, None)
         out["config"]["workload"] = f"{cfg.name}+checkpoints(stride={args.checkpoints})"
         out["config"]["workspace_bytes"] = int(ws.numel())
         out["config"]["workspace_bytes_full_record"] = int(dp.spdy_dp_workspace_bytes(K, L, S, B))
     if args.one_call:
-        out.pop("roofline", None)
-        out.pop("roofline_lds", None)
+        for key in ("roofline", "roofline_lds", "roofline_valu"):
+            out.pop(key, None)
         out["config"]["workload"] = cfg.name + "+one_call"
     if first_layer is not None:
         # the roofline objects describe the plain fill; here the event pair spans the whole call
         # and a varying part of the updates is skipped
-        out.pop("roofline", None)
-        out.pop("roofline_lds", None)
+        for key in ("roofline", "roofline_lds", "roofline_valu"):
+            out.pop(key, None)
         out["config"]["workload"] = f"{cfg.name}+from_incumbent(d={args.from_incumbent})"
         out["config"]["mean_first_layer"] = float(first_layer.mean())
+    if steady is not None and "roofline" in out:
+        steady["roofline_frac"] = out["roofline"]["frac"] * fill_ms / steady["kernel_ms"]
     print(json.dumps(out))
     return 0
 

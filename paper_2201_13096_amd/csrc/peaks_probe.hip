@@ -1,7 +1,13 @@
-// Stand-alone probe of the two rates the fill kernel's roofline is built on: plain (non-packed)
-// vector ALU operations and LDS reads of consecutive dwords, per compute unit and clock.
-// Every access is in bounds and every loop has a fixed trip count.  Build: see build.py; run:
-//     ./peaks_probe
+// Stand-alone probe of the rates the fill kernel's roofline is built on, per compute unit and
+// clock: plain (non-packed) vector ALU instructions in the mixes the fill issues, and LDS reads of
+// consecutive elements at the widths it uses.  bench.py runs it as a child process before it
+// touches the GPU itself and puts the figures next to the nominal peaks in its output line.
+// Every access is in bounds and every loop has a fixed trip count.  Prints one JSON object.
+//
+// The ALU loops are written with inline assembly, one statement per instruction, so the number
+// of issued vector instructions is the number written here (the loop counter and branch are
+// scalar instructions): "lane_ops" below counts issued VALU instructions x 64 lanes, never
+// source-level operations.
 #include <hip/hip_runtime.h>
 
 #include <stdio.h>
@@ -11,55 +17,83 @@
     do {                                                                              \
         hipError_t e_ = (x);                                                          \
         if (e_ != hipSuccess) {                                                       \
-            printf("HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__);     \
+            fprintf(stderr, "HIP error %s at line %d\n", hipGetErrorString(e_), __LINE__); \
             exit(1);                                                                  \
         }                                                                             \
     } while (0)
 
 constexpr int kIters = 4096;
+constexpr int kChains = 8;
 
-// fp32 add + min on 8 independent chains per lane (the D-record update).
+// D-record update without folding: v_add_f32 + v_min_f32 per update (2 instructions).
 __global__ __launch_bounds__(256) void valu_add_min(float *out, float c, int iters)
 {
-    float a[8], b[8];
-    for (int j = 0; j < 8; ++j) {
+    float a[kChains], b[kChains];
+    for (int j = 0; j < kChains; ++j) {
         a[j] = threadIdx.x * 0.5f + j;
         b[j] = 1e30f;
     }
     for (int i = 0; i < iters; ++i) {
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            a[j] = a[j] + c;
-            b[j] = fminf(b[j], a[j]);
+        for (int j = 0; j < kChains; ++j) {
+            asm volatile("v_add_f32 %0, %0, %1" : "+v"(a[j]) : "v"(c));
+            asm volatile("v_min_f32 %0, %0, %1" : "+v"(b[j]) : "v"(a[j]));
         }
     }
     float s = 0;
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < kChains; ++j)
         s += b[j] + a[j];
     out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
 
-// fp32 add + compare + two selects (the level-tracking update as Alg. 1 writes it).
-__global__ __launch_bounds__(256) void valu_add_cmp_sel(float *out, float c, int iters)
+// D-record update as built: two adds folded by one v_min3_f32 (3 instructions per 2 updates).
+__global__ __launch_bounds__(256) void valu_add_add_min3(float *out, float c, int iters)
 {
-    float a[8], b[8];
-    int g[8];
-    for (int j = 0; j < 8; ++j) {
+    float a[kChains], d[kChains], b[kChains];
+    for (int j = 0; j < kChains; ++j) {
+        a[j] = threadIdx.x * 0.5f + j;
+        d[j] = threadIdx.x * 0.25f + j;
+        b[j] = 1e30f;
+    }
+    for (int i = 0; i < iters; ++i) {
+#pragma unroll
+        for (int j = 0; j < kChains; ++j) {
+            asm volatile("v_add_f32 %0, %0, %1" : "+v"(a[j]) : "v"(c));
+            asm volatile("v_add_f32 %0, %0, %1" : "+v"(d[j]) : "v"(c));
+            asm volatile("v_min3_f32 %0, %0, %1, %2" : "+v"(b[j]) : "v"(a[j]), "v"(d[j]));
+        }
+    }
+    float s = 0;
+    for (int j = 0; j < kChains; ++j)
+        s += b[j] + a[j] + d[j];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+// Level-record update as built: add, compare, select of the level, min (4 instructions).
+__global__ __launch_bounds__(256) void valu_add_cmp_sel_min(float *out, float c, int iters)
+{
+    float a[kChains], b[kChains];
+    int g[kChains];
+    for (int j = 0; j < kChains; ++j) {
         a[j] = threadIdx.x * 0.5f + j;
         b[j] = 1e30f;
         g[j] = 0;
     }
     for (int i = 0; i < iters; ++i) {
+        int level = i;
+        asm volatile("" : "+v"(level));
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            a[j] = a[j] + c;
-            const bool lt = a[j] < b[j];
-            b[j] = lt ? a[j] : b[j];
-            g[j] = lt ? i : g[j];
+        for (int j = 0; j < kChains; ++j) {
+            asm volatile("v_add_f32 %0, %0, %1" : "+v"(a[j]) : "v"(c));
+            asm volatile("v_cmp_lt_f32 vcc, %1, %2\n\tv_cndmask_b32 %0, %0, %3, vcc"
+                         : "+v"(g[j])
+                         : "v"(a[j]), "v"(b[j]), "v"(level)
+                         : "vcc");
+            asm volatile("v_min_f32 %0, %0, %1" : "+v"(b[j]) : "v"(a[j]));
         }
     }
     float s = 0;
-    for (int j = 0; j < 8; ++j)
+    for (int j = 0; j < kChains; ++j)
         s += b[j] + a[j] + g[j];
     out[blockIdx.x * blockDim.x + threadIdx.x] = s;
 }
@@ -69,7 +103,7 @@ __global__ __launch_bounds__(256) void valu_add_cmp_sel(float *out, float c, int
 template <typename T>
 __global__ __launch_bounds__(256) void lds_read(int *out, int step, int iters, int words)
 {
-    extern __shared__ int lds[];
+    extern __shared__ __attribute__((aligned(16))) int lds[];
     for (int i = threadIdx.x; i < words; i += blockDim.x)
         lds[i] = i;
     __syncthreads();
@@ -109,6 +143,8 @@ float time_ms(F launch, int reps)
     CHECK(hipEventSynchronize(b));
     float ms;
     CHECK(hipEventElapsedTime(&ms, a, b));
+    CHECK(hipEventDestroy(a));
+    CHECK(hipEventDestroy(b));
     return ms / reps;
 }
 
@@ -118,52 +154,44 @@ int main()
     CHECK(hipGetDeviceProperties(&p, 0));
     const int cus = p.multiProcessorCount;
     const double clk = p.clockRate * 1e3;
-    printf("device %s, %d CUs, %.0f MHz, %zu B LDS per workgroup\n", p.gcnArchName, cus,
-           clk / 1e6, p.sharedMemPerBlock);
     const int blocks = cus * 8, threads = 256;
     float *out;
     CHECK(hipMalloc(&out, sizeof(float) * blocks * threads));
 
-    float ms = time_ms([&] { hipLaunchKernelGGL(valu_add_min, dim3(blocks), dim3(threads), 0, 0,
-                                                out, 1.0f, kIters); }, 20);
-    double ops = (double)blocks * threads * kIters * 16;
-    printf("VALU add+min        : %.3f ms  %.2f Tlane-op/s  %.1f lane-ops/clk/CU\n", ms,
-           ops / ms / 1e9, ops / (ms * 1e-3) / clk / cus);
-    ms = time_ms([&] { hipLaunchKernelGGL(valu_add_cmp_sel, dim3(blocks), dim3(threads), 0, 0,
-                                          out, 1.0f, kIters); }, 20);
-    ops = (double)blocks * threads * kIters * 32;
-    printf("VALU add+cmp+2 sel  : %.3f ms  %.2f Tlane-op/s  %.1f lane-ops/clk/CU\n", ms,
-           ops / ms / 1e9, ops / (ms * 1e-3) / clk / cus);
+    printf("{\"device\": \"%s\", \"compute_units\": %d, \"clock_mhz\": %.0f", p.gcnArchName, cus,
+           clk / 1e6);
+    auto valu = [&](const char *name, auto kernel, int instr_per_iter) {
+        const float ms = time_ms(
+            [&] { hipLaunchKernelGGL(kernel, dim3(blocks), dim3(threads), 0, 0, out, 1.0f, kIters); },
+            20);
+        const double ops = (double)blocks * threads * kIters * kChains * instr_per_iter;
+        printf(", \"%s\": {\"ms\": %.4f, \"tlane_ops_per_s\": %.3f, \"lane_ops_per_clk_cu\": %.2f}",
+               name, ms, ops / ms / 1e9, ops / (ms * 1e-3) / clk / cus);
+    };
+    valu("valu_add_min", valu_add_min, 2);
+    valu("valu_add_add_min3", valu_add_add_min3, 3);
+    valu("valu_add_cmp_sel_min", valu_add_cmp_sel_min, 4);
 
     const int words = 8192;    // 32 KB per workgroup, four workgroups (16 waves) per CU
     const int nb = cus * 4;
-    CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(lds_read<int>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, words * 4));
-    CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(lds_read<int2>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, words * 4));
-    CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(lds_read<int4>),
-                              hipFuncAttributeMaxDynamicSharedMemorySize, words * 4));
-    for (int step : {64, 65, 1}) {
-        ms = time_ms([&] { hipLaunchKernelGGL(lds_read<int>, dim3(nb), dim3(threads), words * 4, 0,
-                                              (int *)out, step, kIters, words); }, 10);
-        const double bytes = (double)nb * threads * kIters * 8 * 4;
-        printf("LDS 32-bit reads, base step %2d dwords : %.3f ms  %.1f TB/s  %.1f B/clk/CU\n", step,
-               ms, bytes / ms / 1e9, bytes / (ms * 1e-3) / clk / cus);
-    }
-    for (int step : {64, 2}) {
-        ms = time_ms([&] { hipLaunchKernelGGL(lds_read<int2>, dim3(nb), dim3(threads), words * 4, 0,
-                                              (int *)out, step, kIters / 2, words); }, 10);
-        const double bytes = (double)nb * threads * (kIters / 2) * 8 * 8;
-        printf("LDS 64-bit reads, base step %2d dwords : %.3f ms  %.1f TB/s  %.1f B/clk/CU\n", step,
-               ms, bytes / ms / 1e9, bytes / (ms * 1e-3) / clk / cus);
-    }
-    for (int step : {64, 4}) {
-        ms = time_ms([&] { hipLaunchKernelGGL(lds_read<int4>, dim3(nb), dim3(threads), words * 4, 0,
-                                              (int *)out, step, kIters / 4, words); }, 10);
-        const double bytes = (double)nb * threads * (kIters / 4) * 8 * 16;
-        printf("LDS 128-bit reads, base step %2d dwords: %.3f ms  %.1f TB/s  %.1f B/clk/CU\n", step,
-               ms, bytes / ms / 1e9, bytes / (ms * 1e-3) / clk / cus);
-    }
+    auto lds = [&](const char *name, auto kernel, int width, int step) {
+        CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                  hipFuncAttributeMaxDynamicSharedMemorySize, words * 4));
+        const int iters = kIters / (width / 4);
+        const float ms = time_ms(
+            [&] {
+                hipLaunchKernelGGL(kernel, dim3(nb), dim3(threads), words * 4, 0, (int *)out, step,
+                                   iters, words);
+            },
+            10);
+        const double bytes = (double)nb * threads * iters * 8 * width;
+        printf(", \"%s\": {\"ms\": %.4f, \"tb_per_s\": %.2f, \"bytes_per_clk_cu\": %.1f}", name, ms,
+               bytes / ms / 1e9, bytes / (ms * 1e-3) / clk / cus);
+    };
+    lds("lds_read_b32", lds_read<int>, 4, 65);
+    lds("lds_read_b64", lds_read<int2>, 8, 66);
+    lds("lds_read_b128", lds_read<int4>, 16, 68);
+    printf("}\n");
     CHECK(hipFree(out));
     return 0;
 }

@@ -71,7 +71,9 @@ constexpr int kWalkThreads = 256;    // D-record walk back: 4 waves = 4 candidat
 constexpr int kLdsStatic = 8192 + 256;    // the fill kernel's static LDS (entry tables, argmin)
 constexpr int kLdsBytes = 160 * 1024 - kLdsStatic;       // dynamic LDS a workgroup can get
 constexpr int kLdsHalf = 80 * 1024 - kLdsStatic;         // lets two workgroups share a compute unit
-constexpr int kHalo = kMaxGroupTurns * kWave;  // +inf apron left of every row (a group's width)
+// +inf apron left of every row: a group's width, plus one chunk because the 128-bit reads of the
+// sweep start one lane (four buckets) below the group
+constexpr int kHalo = kMaxGroupTurns * kWave + kWave;
 // The longest row the waves of a workgroup can hold in registers (and so update in place), with
 // its apron, fits the smaller LDS allocation for either record, and two rows that are any longer
 // do not: the in-place case and the launch with the smaller allocation coincide.
@@ -344,6 +346,10 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots
 //     the sign of a zero): one update with the smallest error of the entry's levels serves them
 //     all.  Entry r covers positions start[r] .. start[r + 1] - 1 of `order`, level s belongs
 //     to entry entry[s]; the entries a group of buckets can use form a prefix.
+//   D record, at most 64 levels (sorted = 2): as above, but the entries are ordered by
+//     (shift mod 4, shift): the sweep reads four consecutive buckets per lane with one aligned
+//     128-bit LDS read and treats the four residues of the shift separately; the usable entries
+//     of a residue then form a prefix of that residue's run.
 // One thread per level (S <= 255).
 __device__ void prepare_order(const int32_t *__restrict__ tau, int l, int S, int s8, int sorted,
                               int32_t *__restrict__ shifts, int32_t *__restrict__ order,
@@ -360,10 +366,16 @@ __device__ void prepare_order(const int32_t *__restrict__ tau, int l, int S, int
         const int32_t *tau_l = tau + (size_t)l * S;
         const int mine = tau_l[s];
         int rank = 0, m = INT32_MAX;
+        for (int o = 0; o < S; ++o)
+            m = min(m, tau_l[o]);
+        const int residues = sorted == 2 ? 3 : 0;
+        const int mine_class = (mine - m) & residues;
         for (int o = 0; o < S; ++o) {
             const int other = tau_l[o];
-            m = min(m, other);
-            rank += (other < mine || (other == mine && o < s)) ? 1 : 0;
+            const int other_class = (other - m) & residues;
+            const bool before = other_class != mine_class ? other_class < mine_class
+                                                          : (other < mine || (other == mine && o < s));
+            rank += before ? 1 : 0;
             twin |= o > s && other == mine;
         }
         if (!sorted)
@@ -729,6 +741,172 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, Leve
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The D-record sweep with 128-bit LDS reads (layers of at most 64 levels).  Aligned 128-bit reads
+// move twice the bytes per clock of narrower ones, so a lane takes four consecutive buckets:
+//   * the first 252 Q buckets of a wave's group are Q "quad chunks": lane i >= 1 owns buckets
+//     252 j + 4 (i - 1) .. + 3 of quad chunk j, and one read gives it the four values
+//     row[4 q .. 4 q + 3] of the aligned quad q = (its own quad) - (shift / 4);
+//   * a shift that is not a multiple of four needs the last (shift mod 4) values of the quad
+//     below, which is exactly what the lane to the left has read: they come over with the add
+//     itself (DPP wave_shr:1).  Lane 0 has no bucket of its own: it reads the quad below lane
+//     1's and only serves as that left neighbour (63 of 64 lanes work);
+//   * the residue decides which operands cross lanes, so the entries of a layer are visited by
+//     residue (the prepare kernel orders them that way) and each residue has its own code;
+//   * the remaining buckets of the group, fewer than 252, are covered by T ordinary chunks of 64
+//     (32-bit reads, lane = bucket) placed at the END of the group; they may overlap the quad
+//     chunks by up to 63 buckets, which are then computed twice with the same result.
+// R chunks of 64 thus become Q quad chunks and T tail chunks, 4 Q + T <= R + 1 registers.
+typedef float float4v __attribute__((ext_vector_type(4)));
+constexpr int kQuadLanes = kWave - 1;             // lanes of a quad chunk that own buckets
+constexpr int kQuadChunk = 4 * kQuadLanes;        // 252 buckets
+constexpr int quad_chunks(int R) { return R * kWave / kQuadChunk; }
+constexpr int tail_chunks(int R)
+{
+    return (R * kWave - quad_chunks(R) * kQuadChunk + kWave - 1) / kWave;
+}
+
+// x of the lane to the left (lane 0 gets 0.0f, which nothing uses)
+__device__ __forceinline__ float from_left(float x)
+{
+    return __int_as_float(
+        __builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x138 /* wave_shr:1 */, 0xf, 0xf, true));
+}
+
+// The four values D_{l-1}[t - shift] for the four buckets t of a lane, from the aligned quad `own`
+// it has read and the quad the lane to its left has read; kRes = shift mod 4.
+template <int kRes>
+__device__ __forceinline__ void shifted_quad(float4v own, float e, float (&v)[4])
+{
+    const float o[4] = {own.x, own.y, own.z, own.w};
+#pragma unroll
+    for (int c = 0; c < 4; ++c)
+        v[c] = (c >= kRes ? o[c - kRes] : from_left(o[4 + c - kRes])) + e;
+}
+
+template <int Q, int T, int kRes>
+__device__ __forceinline__ void sweep_residue(const float4v *quads, const float *tail,
+                                              LevelEntry mine, unsigned long long use,
+                                              float (&bq)[Q > 0 ? Q : 1][4], float (&bt)[T > 0 ? T : 1])
+{
+    // the usable entries of a residue are consecutive positions of the visiting order
+    int i = use ? __builtin_ctzll(use) : 0;
+    int n = __builtin_popcountll(use);
+    for (; n >= 2; n -= 2, i += 2) {
+        const int s0 = __builtin_amdgcn_readlane(mine.shift, i);
+        const int s1 = __builtin_amdgcn_readlane(mine.shift, i + 1);
+        float e0 = lane_value(mine.err, i);
+        float e1 = lane_value(mine.err, i + 1);
+        asm volatile("" : "+v"(e0), "+v"(e1));    // addends of the cross-lane adds live in VGPRs
+        if constexpr (Q > 0) {
+            const float4v *q0 = quads - (s0 >> 2);
+            const float4v *q1 = quads - (s1 >> 2);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                float a[4], b[4];
+                shifted_quad<kRes>(q0[j * kQuadLanes], e0, a);
+                shifted_quad<kRes>(q1[j * kQuadLanes], e1, b);
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    vmin3(bq[j][c], a[c], b[c]);
+            }
+        }
+        if constexpr (T > 0) {
+            const float *p0 = tail - s0;
+            const float *p1 = tail - s1;
+#pragma unroll
+            for (int j = 0; j < T; ++j)
+                vmin3(bt[j], p0[j * kWave] + e0, p1[j * kWave] + e1);
+        }
+    }
+    if (n) {
+        const int s0 = __builtin_amdgcn_readlane(mine.shift, i);
+        float e0 = lane_value(mine.err, i);
+        asm volatile("" : "+v"(e0));
+        if constexpr (Q > 0) {
+            const float4v *q0 = quads - (s0 >> 2);
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                float a[4];
+                shifted_quad<kRes>(q0[j * kQuadLanes], e0, a);
+#pragma unroll
+                for (int c = 0; c < 4; ++c)
+                    vmin(bq[j][c], a[c]);
+            }
+        }
+        if constexpr (T > 0) {
+            const float *p0 = tail - s0;
+#pragma unroll
+            for (int j = 0; j < T; ++j)
+                vmin(bt[j], p0[j * kWave] + e0);
+        }
+    }
+}
+
+// One group of R chunks of one layer (D record, at most 64 levels): sweep with 128-bit reads,
+// store the record, write the new row values; the barrier protocol is fill_group's.
+// prev + t0 is 16-byte aligned (rows, aprons and chunk starts are multiples of four floats).
+template <int R, bool inplace>
+__device__ __forceinline__ void fill_group_quads(const float *prev, float *cur, float *rec,
+                                                 LevelEntry first, int t0, int lane,
+                                                 Pending pending)
+{
+    if constexpr (R == 0) {
+        pending.settle();
+        if (inplace)
+            __syncthreads();
+    } else {
+        constexpr int Q = quad_chunks(R), T = tail_chunks(R);
+        constexpr int tail0 = (R - T) * kWave;    // first bucket of the tail chunks in the group
+        float bq[Q > 0 ? Q : 1][4], bt[T > 0 ? T : 1];
+#pragma unroll
+        for (int j = 0; j < Q; ++j)
+#pragma unroll
+            for (int c = 0; c < 4; ++c)
+                bq[j][c] = __builtin_inff();
+#pragma unroll
+        for (int j = 0; j < T; ++j)
+            bt[j] = __builtin_inff();
+        const int last = t0 + R * kWave - 1;      // last bucket of the group
+        const float4v *quads = reinterpret_cast<const float4v *>(prev + t0) + (lane - 1);
+        const float *tail = prev + t0 + tail0 + lane;
+        const unsigned long long use = __ballot(first.shift <= last);
+        const int residue = first.shift & 3;
+        sweep_residue<Q, T, 0>(quads, tail, first, use & __ballot(residue == 0), bq, bt);
+        sweep_residue<Q, T, 1>(quads, tail, first, use & __ballot(residue == 1), bq, bt);
+        sweep_residue<Q, T, 2>(quads, tail, first, use & __ballot(residue == 2), bq, bt);
+        sweep_residue<Q, T, 3>(quads, tail, first, use & __ballot(residue == 3), bq, bt);
+        pending.settle();
+        const int tq = t0 + 4 * (lane - 1);       // this lane's first bucket of quad chunk 0
+        const int tt = t0 + tail0 + lane;
+        if (rec) {       // streamed: the record is not read again before the walk back
+            if (lane > 0) {
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    const float4v v = {bq[j][0], bq[j][1], bq[j][2], bq[j][3]};
+                    __builtin_nontemporal_store(
+                        v, reinterpret_cast<float4v *>(rec + tq + j * kQuadChunk));
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < T; ++j)
+                __builtin_nontemporal_store(bt[j], &rec[tt + j * kWave]);
+        }
+        if (inplace)
+            __syncthreads();
+        if (lane > 0) {
+#pragma unroll
+            for (int j = 0; j < Q; ++j) {
+                const float4v v = {bq[j][0], bq[j][1], bq[j][2], bq[j][3]};
+                *reinterpret_cast<float4v *>(cur + tq + j * kQuadChunk) = v;
+            }
+        }
+#pragma unroll
+        for (int j = 0; j < T; ++j)
+            cur[tt + j * kWave] = bt[j];
+    }
+}
+
 // One group of one layer: sweep, store the record, and write the new row values to `cur`.
 // With `inplace` cur aliases prev, so a workgroup barrier separates the last read of the row
 // from the first write (every wave of the workgroup calls this exactly once per layer then,
@@ -763,7 +941,7 @@ __device__ __forceinline__ void fill_group(const float *prev, float *cur, uint8_
     }
 }
 
-template <bool kLevel, bool inplace, int kMax>
+template <bool kLevel, bool inplace, int kMax, bool kQuads>
 __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cur, uint8_t *choice,
                                              float *rec, LevelEntry first, LayerTable tl,
                                              ErrRow er, int s8, int t0, int lane, Pending pending)
@@ -771,9 +949,13 @@ __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cu
     switch (r) {
 #define SPDY_CASE(RR)                                                                          \
     case RR:                                                                                   \
-        if constexpr (RR <= kMax)                                                              \
-            fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, tl, er, s8, t0,     \
-                                            lane, pending);                                    \
+        if constexpr (RR <= kMax) {                                                            \
+            if constexpr (kQuads)                                                              \
+                fill_group_quads<RR, inplace>(prev, cur, rec, first, t0, lane, pending);       \
+            else                                                                               \
+                fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, tl, er, s8, t0, \
+                                                lane, pending);                                \
+        }                                                                                      \
         break;
         SPDY_CASE(0)
         SPDY_CASE(1)
@@ -786,13 +968,6 @@ __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cu
         SPDY_CASE(8)
         SPDY_CASE(9)
         SPDY_CASE(10)
-#undef SPDY_CASE
-#define SPDY_CASE(RR)                                                                          \
-    case RR:                                                                                   \
-        if constexpr (RR <= kMax)                                                              \
-            fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, tl, er, s8, t0,     \
-                                            lane, pending);                                    \
-        break;
         SPDY_CASE(11)
         SPDY_CASE(12)
         SPDY_CASE(13)
@@ -856,13 +1031,14 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     float *__restrict__ rows, int32_t *__restrict__ tstar, float *__restrict__ cost, Resume resume,
     Blocks blocks)
 {
-    extern __shared__ float lds[];
+    extern __shared__ __attribute__((aligned(16))) float lds[];
     __shared__ float s_best[kMaxFillWaves];
     __shared__ int s_time[kMaxFillWaves];
     // per team and for two layers: merged errors (D record), or in the same storage one 64-bit
     // set of levels to visit (level record)
     __shared__ __attribute__((aligned(8))) float s_entries[2][kMaxFillWaves][kWave];
     constexpr bool kLds = kPath != 0, inplace = kPath == 1;
+    constexpr bool kQuads = !kLevel && kNarrow;  // the D-record sweep with 128-bit LDS reads
     if (meta[kMetaPath] != kPath)
         return;                                  // another launch does the work
     const int bp = meta[kMetaBudget];
@@ -882,6 +1058,12 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
     const int team = wave / tw;
     const int wv = wave - team * tw;             // this wave's index in its team
+    // Which share of the row this wave sweeps.  The low chunks of a row cost less than the high
+    // ones (fewer levels reach them), and wave w of a workgroup runs on SIMD w mod 4: with the
+    // shares in wave order one SIMD would hold the cheap shares of every team and another the
+    // expensive ones.  Every second group of four waves therefore takes its shares in reverse.
+    const bool mirrored = (tw & (tw - 1)) == 0 && ((wave >> 2) & 1);
+    const int share = mirrored ? wv ^ (min(tw, 4) - 1) : wv;
     const int k = blockIdx.x * teams + team;
     const bool active = team < teams && k < K;
 
@@ -953,7 +1135,7 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     const int s8 = tables.s8;
     // S <= 64: the first wave of a team prepares, for the next layer, the team's table of merged
     // errors (D record) or the set of levels worth visiting (level record)
-    const bool producer = kNarrow && wv == 0 && team < teams;
+    const bool producer = kNarrow && share == 0 && team < teams;
     unsigned long long *keep =
         reinterpret_cast<unsigned long long *>(&s_entries[0][0][0]) + (team < teams ? team : 0);
     float *table = &s_entries[0][team < teams ? team : 0][0];
@@ -978,7 +1160,7 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     }
     Pending{&next_fetch, &next_first}.settle();   // no load is in flight at the loop's head
     // chunk boundaries of this wave
-    const int32_t *range = meta + kMetaHeader + 2 * L + (size_t)lb * kRangeStride + wv;
+    const int32_t *range = meta + kMetaHeader + 2 * L + (size_t)lb * kRangeStride + share;
     int c_next = range[0], c_end_next = range[1];
     // Two workgroups share a compute unit, and the hardware serves the older one first: left
     // alone, the first `units` workgroups of a launch run at full speed, the second `units` on what
@@ -1048,7 +1230,7 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
         constexpr int kMax = group_limit<kLevel, kTurns>();
         const Pending pending{&next_fetch, &next_first};
         if constexpr (inplace) {                 // c_end - c <= kMax by construction
-            fill_group_n<kLevel, true, kMax>(min(c_end - c, kMax), prev, cur, choice_l, drec_l, first,
+            fill_group_n<kLevel, true, kMax, kQuads>(min(c_end - c, kMax), prev, cur, choice_l, drec_l, first,
                                        tl, er, s8, c * kWave, lane, pending);
         } else {
             // Rows in global memory: the row is computed in tiles of at most kMax chunks per
@@ -1060,7 +1242,7 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
             int tile = 0, span = 0;
             if constexpr (kPath == 0) {
                 span = meta[kMetaHeader + (2 + (size_t)kRangeStride) * L + l];
-                tile = (meta[kMetaStage] / (int)sizeof(float) - span - 4) / kWave / tw * tw;
+                tile = (meta[kMetaStage] / (int)sizeof(float) - span - 8) / kWave / tw * tw;
                 tile = min(tile, tw * kMax);
             }
             if (kPath == 0 && tile >= tw) {
@@ -1070,8 +1252,9 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
                 for (int c0 = 0; c0 < n_l; c0 += tile) {
                     const int nt = min(tile, n_l - c0);
                     // (lo a multiple of four floats: rows and aprons are, so the copy moves 16
-                    // bytes per lane, eight loads in flight per lane)
-                    const int lo = max((c0 * kWave - span) & ~3, -kHalo);
+                    // bytes per lane, eight loads in flight per lane; four floats more than the
+                    // largest shift, for the lane left of a group's first quad)
+                    const int lo = max(((c0 * kWave - span) & ~3) - 4, -kHalo);
                     const int len4 = ((c0 + nt) * kWave - lo) / 4;
                     const float4 *from = reinterpret_cast<const float4 *>(prev + lo);
                     float4 *to = reinterpret_cast<float4 *>(lds);
@@ -1088,9 +1271,9 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
                         }
                     }
                     __syncthreads();
-                    const int cb = c0 + (int)((long long)wv * nt / tw);
-                    const int ce = c0 + (int)((long long)(wv + 1) * nt / tw);
-                    fill_group_n<kLevel, false, kMax>(ce - cb, lds - lo, cur, choice_l, drec_l,
+                    const int cb = c0 + (int)((long long)share * nt / tw);
+                    const int ce = c0 + (int)((long long)(share + 1) * nt / tw);
+                    fill_group_n<kLevel, false, kMax, kQuads>(ce - cb, lds - lo, cur, choice_l, drec_l,
                                                       first, tl, er, s8, cb * kWave, lane,
                                                       pending);
                     __syncthreads();             // the next tile overwrites the staged part
@@ -1100,7 +1283,7 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
                     const int n = c_end - c;
                     const int groups = (n + kMax - 1) / kMax;
                     const int r = (n + groups - 1) / groups;
-                    fill_group_n<kLevel, false, kMax>(r, prev, cur, choice_l, drec_l, first, tl,
+                    fill_group_n<kLevel, false, kMax, kQuads>(r, prev, cur, choice_l, drec_l, first, tl,
                                                       er, s8, c * kWave, lane, pending);
                     c += r;
                 }
@@ -1378,14 +1561,22 @@ __global__ __launch_bounds__(kWalkThreads) void dp_backtrace_values(
             return;
         }
     }
-    // lane 0 wrote the profile; make it visible to its own reads, then re-sum in layer order
+    // Lane 0 wrote the profile; make it visible to the wave, then re-sum the cost in layer order.
+    // Lane i fetches the error of layer 64 b + i (all layers of a block of 64 in one round trip
+    // instead of one after the other); the sum itself runs over the lanes in order.
     __threadfence();
-    if (lane == 0) {
-        float acc = -0.0f;
-        for (int l = 0; l < L; ++l)
-            acc += src.row(k, l, L, S).at(prof[l]);
-        cost[k] = acc;
+    float acc = -0.0f;
+    for (int base = 0; base < L; base += kWave) {
+        const int l = base + lane;
+        float e = 0.0f;
+        if (l < L)
+            e = src.row(k, l, L, S).at(prof[l]);
+        const int n = min(kWave, L - base);
+        for (int i = 0; i < n; ++i)
+            acc += lane_value(e, i);
     }
+    if (lane == 0)
+        cost[k] = acc;
 }
 
 int launch_status()
@@ -1490,7 +1681,8 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
 
     if (!(kBlocks && blocks.pass == 1))          // the block passes reuse pass 0's tables
         hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, K, 2 * units, L, S, s8,
-                           B, waves, max_group, lds_small, lds_large, lds_stage, kLevel ? 0 : 1, meta,
+                           B, waves, max_group, lds_small, lds_large, lds_stage,
+                           kLevel ? 0 : (kNarrow ? 2 : 1), meta,
                            shifts, order, start, entry);
     const LevelTables tables{shifts, order, start, entry, s8};
     hipLaunchKernelGGL(in_place, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, tables,
