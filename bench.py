@@ -363,23 +363,30 @@ def main() -> int:
     def rate(obj, key):
         return None if peaks is None or obj not in peaks else peaks[obj].get(key)
 
-    # The D-record fill is bound by LDS reads (one 32-bit read of the shifted row per update, an
-    # add and half a v_min3 beside it); the level-record fill by the vector ALU (four instructions
-    # per update).  Both objects are always reported; `roofline` is the binding one.
+    # The D-record fill is bound by LDS reads (4 bytes of the shifted row per update, an add and
+    # half a v_min3 beside it); the level-record fill by the vector ALU (four instructions per
+    # update).  Both objects are always reported; `roofline` is the binding one.  With at most 64
+    # levels the D-record sweep reads 128 bits per lane, so its peak is the 128-bit one; the
+    # fraction of the 32-bit-read peak (what a lane = bucket layout can reach at best) is beside it.
+    wide_reads = args.record == "d" and S <= 64
+    lds_peak = LDS_PEAK_B128 if wide_reads else LDS_PEAK_B32
+    lds_probe = "lds_read_b128" if wide_reads else "lds_read_b32"
     lds_obj = {
         "bound": "lds",
         "kernel": "dp_fill",
         "achieved": lds_bytes / seconds / 1e12,
-        "peak": LDS_PEAK_B32 / 1e12,
+        "peak": lds_peak / 1e12,
         "unit": "TB/s",
-        "frac": lds_bytes / seconds / LDS_PEAK_B32,
+        "frac": lds_bytes / seconds / lds_peak,
         "bytes_per_update": 4.0 * (1.0 + 1.0 / S),
-        "peak_is": "nominal: 256 CU x 128 B/clk x 2.4 GHz, reads of up to 64 bits per lane",
-        "peak_measured": rate("lds_read_b32", "tb_per_s"),
-        "frac_of_measured": None if rate("lds_read_b32", "tb_per_s") is None
-        else lds_bytes / seconds / 1e12 / rate("lds_read_b32", "tb_per_s"),
-        "peak_128bit_nominal": LDS_PEAK_B128 / 1e12,
-        "peak_128bit_measured": rate("lds_read_b128", "tb_per_s"),
+        "peak_is": ("nominal: 256 CU x 256 B/clk x 2.4 GHz, aligned 128-bit reads" if wide_reads else
+                    "nominal: 256 CU x 128 B/clk x 2.4 GHz, reads of up to 64 bits per lane"),
+        "peak_measured": rate(lds_probe, "tb_per_s"),
+        "frac_of_measured": None if rate(lds_probe, "tb_per_s") is None
+        else lds_bytes / seconds / 1e12 / rate(lds_probe, "tb_per_s"),
+        "peak_b32_nominal": LDS_PEAK_B32 / 1e12,
+        "frac_of_b32_nominal": lds_bytes / seconds / LDS_PEAK_B32,
+        "peak_b32_measured": rate("lds_read_b32", "tb_per_s"),
     }
     probe_mix = "valu_add_add_min3" if args.record == "d" else "valu_add_cmp_sel_min"
     valu_obj = {
@@ -403,6 +410,11 @@ def main() -> int:
         "kernel_ms_median": float(np.median(fill_samples)),
         "kernel_ms_min": float(np.min(fill_samples)),
         "executed_updates_per_s": executed / seconds,
+        # per clock and compute unit, beside what the sweep loop alone reaches in the rate probe
+        # (no barriers, stores or table hand-over): the practical ceiling of this instruction mix
+        "updates_per_clk_cu": executed / seconds / CLOCK_HZ / COMPUTE_UNITS,
+        "bare_sweep_updates_per_clk_cu": rate("sweep_b128" if wide_reads else "sweep_b32",
+                                              "updates_per_clk_cu"),
         "traffic": tracked_traffic(cfg.name, args.record) if K == cfg.K else None,
     })
     if roofline["traffic"] is not None:           # the record stream: not the bound

@@ -127,6 +127,101 @@ __global__ __launch_bounds__(256) void lds_read(int *out, int step, int iters, i
     out[blockIdx.x * blockDim.x + threadIdx.x] = acc;
 }
 
+// The sweep of the fill kernel by itself (no barriers, no record stores, no table hand-over): a
+// wave keeps a running minimum per bucket and visits pairs of entries; per pair and bucket one
+// LDS read and one add per entry and one v_min3.  Two layouts:
+//   sweep_b32:  lane = bucket, 16 chunks of 64 buckets per wave, 32-bit reads;
+//   sweep_b128: lane = four consecutive buckets, 4 chunks of 256 buckets per wave, one aligned
+//               128-bit read per entry; a shift that is not a multiple of four takes its last
+//               kRes values from the lane to the left with the add (DPP wave_shr:1).
+// Eight waves per workgroup, two workgroups per compute unit, as the fill runs.
+constexpr int kSweepRow = 8 * 16 * 64;   // floats swept per workgroup
+constexpr int kSweepHalo = 2048;         // shifts stay below this
+typedef float float4v __attribute__((ext_vector_type(4)));
+
+__device__ __forceinline__ void min3(float &b, float x, float y)
+{
+    asm("v_min3_f32 %0, %0, %1, %2" : "+v"(b) : "v"(x), "v"(y));
+}
+__device__ __forceinline__ float from_left(float x)
+{
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), 0x138, 0xf, 0xf, true));
+}
+__device__ __forceinline__ float lane_float(float v, int lane)
+{
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+__global__ __launch_bounds__(512, 2) void sweep_b32(float *out, const int *shifts,
+                                                    const float *errs, int pairs, int iters)
+{
+    extern __shared__ __attribute__((aligned(16))) float row[];
+    for (int i = threadIdx.x; i < kSweepRow + kSweepHalo; i += blockDim.x)
+        row[i] = (float)(i & 1023);
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float *mine = row + kSweepHalo + wave * 16 * 64 + lane;
+    float best[16];
+    for (int j = 0; j < 16; ++j)
+        best[j] = 1e30f;
+    const int sh = shifts[lane];
+    const float er = errs[lane];
+    for (int it = 0; it < iters; ++it)
+        for (int i = 0; i < 2 * pairs; i += 2) {
+            const float *p0 = mine - __builtin_amdgcn_readlane(sh, i);
+            const float *p1 = mine - __builtin_amdgcn_readlane(sh, i + 1);
+            const float e0 = lane_float(er, i), e1 = lane_float(er, i + 1);
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                min3(best[j], p0[j * 64] + e0, p1[j * 64] + e1);
+        }
+    float s = 0;
+    for (int j = 0; j < 16; ++j)
+        s += best[j];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
+template <int kRes>
+__global__ __launch_bounds__(512, 2) void sweep_b128(float *out, const int *shifts,
+                                                     const float *errs, int pairs, int iters)
+{
+    extern __shared__ __attribute__((aligned(16))) float row[];
+    for (int i = threadIdx.x; i < kSweepRow + kSweepHalo; i += blockDim.x)
+        row[i] = (float)(i & 1023);
+    __syncthreads();
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const float4v *mine = reinterpret_cast<const float4v *>(row + kSweepHalo) + wave * 4 * 64 + lane;
+    float best[4][4];
+    for (int j = 0; j < 4; ++j)
+        for (int c = 0; c < 4; ++c)
+            best[j][c] = 1e30f;
+    const int sh = shifts[lane] >> 2;    // in quads
+    const float er = errs[lane];
+    for (int it = 0; it < iters; ++it)
+        for (int i = 0; i < 2 * pairs; i += 2) {
+            const float4v *p0 = mine - __builtin_amdgcn_readlane(sh, i);
+            const float4v *p1 = mine - __builtin_amdgcn_readlane(sh, i + 1);
+            float e0 = lane_float(er, i), e1 = lane_float(er, i + 1);
+            asm volatile("" : "+v"(e0), "+v"(e1));
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float4v a = p0[j * 64], b = p1[j * 64];
+                const float av[4] = {a.x, a.y, a.z, a.w}, bv[4] = {b.x, b.y, b.z, b.w};
+#pragma unroll
+                for (int c = 0; c < 4; ++c) {
+                    const float x = (c >= kRes ? av[c - kRes] : from_left(av[4 + c - kRes])) + e0;
+                    const float y = (c >= kRes ? bv[c - kRes] : from_left(bv[4 + c - kRes])) + e1;
+                    min3(best[j][c], x, y);
+                }
+            }
+        }
+    float s = 0;
+    for (int j = 0; j < 4; ++j)
+        for (int c = 0; c < 4; ++c)
+            s += best[j][c];
+    out[blockIdx.x * blockDim.x + threadIdx.x] = s;
+}
+
 template <typename F>
 float time_ms(F launch, int reps)
 {
@@ -191,6 +286,46 @@ int main()
     lds("lds_read_b32", lds_read<int>, 4, 65);
     lds("lds_read_b64", lds_read<int2>, 8, 66);
     lds("lds_read_b128", lds_read<int4>, 16, 68);
+    {
+        // the bare sweep: updates per clock per compute unit
+        const int pairs = 16, iters = 64, wgs = cus * 2, wg_threads = 512;
+        int hs[64];
+        float he[64];
+        for (int i = 0; i < 64; ++i) {
+            hs[i] = (i * 52 + 7) & ~3;
+            if (hs[i] > kSweepHalo - 64)
+                hs[i] = kSweepHalo - 64;
+            he[i] = 0.25f * i;
+        }
+        int *sh;
+        float *er;
+        CHECK(hipMalloc(&sh, sizeof hs));
+        CHECK(hipMalloc(&er, sizeof he));
+        CHECK(hipMemcpy(sh, hs, sizeof hs, hipMemcpyHostToDevice));
+        CHECK(hipMemcpy(er, he, sizeof he, hipMemcpyHostToDevice));
+        const size_t bytes = (kSweepRow + kSweepHalo) * sizeof(float);
+        const double updates = (double)wgs * wg_threads * 16 * (2.0 * pairs) * iters;
+        auto sweep = [&](auto kernel) {
+            CHECK(hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes));
+            const float ms = time_ms(
+                [&] {
+                    hipLaunchKernelGGL(kernel, dim3(wgs), dim3(wg_threads), bytes, 0, out, sh, er,
+                                       pairs, iters);
+                },
+                20);
+            return updates / (ms * 1e-3) / clk / cus;
+        };
+        const double u32 = sweep(sweep_b32);
+        const double u0 = sweep(sweep_b128<0>), u1 = sweep(sweep_b128<1>);
+        const double u2 = sweep(sweep_b128<2>), u3 = sweep(sweep_b128<3>);
+        printf(", \"sweep_b32\": {\"updates_per_clk_cu\": %.2f}", u32);
+        printf(", \"sweep_b128\": {\"updates_per_clk_cu\": %.2f, \"by_shift_mod_4\": [%.2f, %.2f, %.2f, "
+               "%.2f]}",
+               4.0 / (1.0 / u0 + 1.0 / u1 + 1.0 / u2 + 1.0 / u3), u0, u1, u2, u3);
+        CHECK(hipFree(sh));
+        CHECK(hipFree(er));
+    }
     printf("}\n");
     CHECK(hipFree(out));
     return 0;

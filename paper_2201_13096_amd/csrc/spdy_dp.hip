@@ -687,6 +687,7 @@ __device__ __forceinline__ void sweep_group(const float *__restrict__ prev, Leve
         arg[j] = kNoLevel;
     }
     const int last = t0 + R * kWave - 1;      // last bucket of the group
+    __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0): see fill_group_quads
     const char *pl = reinterpret_cast<const char *>(prev + t0 + lane);
     auto row_at = [&](int shift) {
         return reinterpret_cast<const float *>(pl - (size_t)((unsigned)shift * 4u));
@@ -872,6 +873,11 @@ __device__ __forceinline__ void fill_group_quads(const float *prev, float *cur, 
         const float *tail = prev + t0 + tail0 + lane;
         const unsigned long long use = __ballot(first.shift <= last);
         const int residue = first.shift & 3;
+        // Scalar loads and LDS reads share one counter, and scalar loads return out of order: while
+        // one is in flight (the wall clock of the priority turns, the next layer's chunk range)
+        // every wait for an LDS read in the sweep has to be a wait for ALL of them, and a wave
+        // cannot start on the first quads while the later ones arrive.  Let them land first.
+        __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0), nothing else
         sweep_residue<Q, T, 0>(quads, tail, first, use & __ballot(residue == 0), bq, bt);
         sweep_residue<Q, T, 1>(quads, tail, first, use & __ballot(residue == 1), bq, bt);
         sweep_residue<Q, T, 2>(quads, tail, first, use & __ballot(residue == 2), bq, bt);
