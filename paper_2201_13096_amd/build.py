@@ -36,7 +36,8 @@ def build_library(verbose: bool = False) -> str:
 
 
 def build_probe() -> str:
-    """Compile the stand-alone VALU / LDS rate probe (an executable, run by hand on the GPU)."""
+    """Compile the stand-alone VALU / LDS / bare-sweep rate probe (an executable; bench.py runs
+    it as a child process and reports its figures beside the nominal peaks)."""
     tmp = PROBE_PATH + f".tmp{os.getpid()}"
     cmd = ["hipcc", *HIPCC_FLAGS, PROBE_SOURCE, "-o", tmp]
     res = subprocess.run(cmd, capture_output=True, text=True)

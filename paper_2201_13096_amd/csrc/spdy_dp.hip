@@ -14,15 +14,18 @@
 //   * the row of D of a candidate stays in LDS for the whole solve, with a +inf apron of one
 //     group width on its left, so a level whose shift falls inside a group of buckets needs no
 //     per-lane bounds test; levels whose shift lies beyond the group are never visited;
-//   * the time axis is cut into chunks of 64 buckets; lane i of a wave works on bucket
-//     64*c + i of a chunk, so every ds_read_b32 of the shifted row touches 64 consecutive
-//     dwords (conflict-free for any shift) and every store of the record is 64 consecutive
-//     elements;
-//   * a wave keeps R chunks in registers (running minimum, and the level when tracked, for R
-//     buckets per lane) and sweeps the layer once; lane i holds the i-th entry of the layer
-//     (a level, or with the D record all levels of one shift, which one update serves),
-//     one ballot finds the applicable entries and v_readlane moves shift and error to scalar
-//     registers, so the sweep issues no memory instruction besides the LDS reads;
+//   * the time axis is cut into chunks of 64 buckets; a wave keeps a group of R chunks in
+//     registers (running minimum, and the level when tracked) and sweeps the layer once; lane i
+//     holds the i-th entry of the layer (a level, or with the D record all levels of one shift,
+//     which one update serves), ballots find the applicable entries and v_readlane moves shift
+//     and error to scalar registers, so the sweep issues no memory instruction besides the LDS
+//     reads;
+//   * when D itself is recorded and a layer has at most 64 levels, a lane takes four consecutive
+//     buckets and reads them with one aligned ds_read_b128 (twice the LDS bytes per clock of
+//     narrower reads on this chip); the words a shift that is not a multiple of four needs from
+//     the quad below come from the lane to the left through a DPP operand of the add.  Otherwise
+//     lane i works on bucket 64*c + i of a chunk: every ds_read_b32 of the shifted row touches
+//     64 consecutive dwords (conflict-free for any shift);
 //   * the waves of a workgroup are split at run time into teams, one candidate per team, so
 //     that each wave owns as many chunks as its registers hold whatever the reduced row length
 //     is; when every wave holds all its chunks of the row in registers the row is updated in

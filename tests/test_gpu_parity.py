@@ -203,6 +203,41 @@ def test_random_tables_bit_exact(dp, shape):
             check_tables(dp, tau, err[K - 1], B, ws, K - 1, K)
 
 
+def test_every_group_size_of_the_sweep(dp):
+    """Row lengths chosen so that a wave's share of the row takes every size from one chunk up
+    to the most a wave keeps in registers (the sweep is specialised per size: so many chunks
+    read four buckets per lane, so many one), with one candidate per workgroup (eight waves on a
+    row) and with several (teams of fewer waves), shifts of every residue mod 4 and layers whose
+    shifts all share one residue."""
+    rng = np.random.default_rng(4242)
+    dev = torch.device("cuda:0")
+    lay = dp.spdy_dp_workspace_layout(1, 2, 2, 64, dp.spdy_dp_workspace_bytes(1, 2, 2, 64))
+    seen = set()
+    for K in (1, 600):
+        for chunks in list(range(1, 17)) + list(range(17, 8 * 28 + 1, 5)) + [8 * 28]:
+            B = 64 * chunks - int(rng.integers(1, 64))          # reduced row of `chunks` chunks
+            L, S = 3, 7
+            tau = rng.integers(0, max(2, B // 3), size=(L, S)).astype(np.int32)
+            tau[:, 0] = 0                                       # m_l = 0: the row is not reduced
+            if chunks % 3 == 0:
+                tau[1] = tau[1] // 4 * 4 + int(rng.integers(0, 4))   # one residue for a layer
+                tau[1, 0] = 0
+            kk = K if chunks <= 40 or chunks >= 219 else min(K, 3)
+            err = rng.integers(0, 5, size=(kk, L, S)).astype(np.float32) if chunks % 2 else \
+                rng.random((kk, L, S), dtype=np.float32)
+            p_ref, c_ref = oracle.solve_ref(tau, err, B, threads=CPU_THREADS)
+            p_gpu, c_gpu, ws = gpu_solve(dp, tau, err, B)
+            assert_same(p_gpu, c_gpu, p_ref, c_ref, f"K={kk} chunks={chunks} B={B}")
+            check_tables(dp, tau, err[kk - 1], B, ws, kk - 1, kk)
+            H, plan = lay["header_words"], lay["plan_words"]
+            off = dp.spdy_dp_workspace_layout(kk, L, S, B, ws.numel())["meta_offset"]
+            meta = ws[off:off + 4 * (H + (3 + plan) * L)].cpu().numpy().view(np.int32)
+            team_waves = int(meta[4])
+            shares = meta[H + 2 * L:H + (2 + plan) * L].reshape(L, plan)[:, :team_waves + 1]
+            seen.update(int(x) for x in np.diff(shares, axis=1).ravel())
+    assert set(range(1, 29)) <= seen, sorted(set(range(1, 29)) - seen)
+
+
 def test_infeasible_and_mixed_batches(dp):
     # candidate 0 feasible, candidate 1 has every level of layer 2 forbidden, budget too small
     tau = np.array([[5, 3, 1], [4, 2, 1], [6, 2, 2]], dtype=np.int32)
