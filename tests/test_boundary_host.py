@@ -240,3 +240,28 @@ def test_executed_update_counts_bracket_the_necessary_work():
                         needed_folded += 1
         assert needed <= plain, (case, needed, plain)
         assert needed_folded <= folded, (case, needed_folded, folded)
+
+
+def test_traffic_table_only_counts_for_the_source_it_was_taken_on(tmp_path, monkeypatch):
+    """bench.py reports HBM traffic from a tracked table of counter runs; a line must only count
+    for its workload and record and while the kernel source is the one the counters saw."""
+    import bench
+    table = tmp_path / "dp_fill_hbm_traffic.txt"
+    here = bench.kernel_source_id()
+    assert len(here) == 12 and int(here, 16) >= 0
+    table.write_text("# comment\n"
+                     f"rn50_k1024 d {here} 1000 2000\n"
+                     f"rn50_k1024 level {'0' * 12} 5 6\n"
+                     "short line\n")
+    monkeypatch.setattr(bench, "PROFILES", str(tmp_path))
+    assert bench.tracked_traffic("rn50_k1024", "d") == 3000.0
+    assert bench.tracked_traffic("rn50_k1024", "level") is None      # another source
+    assert bench.tracked_traffic("bert_k4096", "d") is None          # no line
+    monkeypatch.setattr(bench, "PROFILES", str(tmp_path / "missing"))
+    assert bench.tracked_traffic("rn50_k1024", "d") is None
+
+
+def test_rate_probe_output_is_optional(monkeypatch, tmp_path):
+    import bench
+    monkeypatch.setattr(bench, "PROBE", str(tmp_path / "no_such_probe"))
+    assert bench.measured_peaks() is None
