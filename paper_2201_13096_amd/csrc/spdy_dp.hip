@@ -107,7 +107,8 @@ enum MetaWord {
     kMetaMaxGroup = 9,  // most chunks a wave keeps in registers
     kMetaLdsSmall = 10, // dynamic LDS bytes of the in-place launch
     kMetaLdsLarge = 11, // dynamic LDS bytes of the two-row launch (0: not enqueued)
-    kMetaHalo = 12      // floats of the +inf apron left of a row
+    kMetaHalo = 12,     // floats of the +inf apron left of a row
+    kMetaSplit = 13     // 1: the in-place launch has twice kMetaWaves waves (see dp_fill, kSplit)
 };
 
 enum Variant { kValueRecord = 0, kLevelRecord = 1 };
@@ -230,7 +231,7 @@ __device__ __forceinline__ long long block_scan_256(long long v, long long *part
 // of layers.
 __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots, int L, int S,
                                int B, int waves, int max_group, int lds_small, int lds_large,
-                               int lds_stage, int32_t *__restrict__ meta)
+                               int lds_stage, int split, int32_t *__restrict__ meta)
 {
     __shared__ long long s_sum[8];
     __shared__ int s_budget, s_team_waves;
@@ -296,6 +297,7 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots
         meta[kMetaLdsSmall] = lds_small;
         meta[kMetaLdsLarge] = lds_large;
         meta[kMetaHalo] = kHalo;
+        meta[kMetaSplit] = split;
         s_budget = bp;
         s_team_waves = waves / teams;
     }
@@ -432,7 +434,7 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
                                                   int slots, int L, int S,
                                                   int s8, int B, int waves, int max_group,
                                                   int lds_small, int lds_large, int lds_stage,
-                                                  int sorted,
+                                                  int sorted, int split,
                                                   int32_t *__restrict__ meta,
                                                   int32_t *__restrict__ shifts,
                                                   int32_t *__restrict__ order,
@@ -441,7 +443,7 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
 {
     if (blockIdx.x == 0)
         prepare_budget(tau, K, slots, L, S, B, waves, max_group, lds_small, lds_large, lds_stage,
-                       meta);
+                       split, meta);
     else
         prepare_order(tau, blockIdx.x - 1, S, s8, sorted, shifts, order, start, entry_of);
 }
@@ -788,15 +790,15 @@ __device__ __forceinline__ void shifted_quad(float4v own, float e, float (&v)[4]
         v[c] = (c >= kRes ? o[c - kRes] : from_left(o[4 + c - kRes])) + e;
 }
 
-template <int Q, int T, int kRes>
+// kSplit: the waves of a workgroup come in two halves that sweep the same chunks, each visiting
+// every other pair of the run's entries (a run's odd last entry counts as a pair); `skip`: the
+// run's first pair is the other half's.
+template <int Q, int T, int kRes, bool kSplit>
 __device__ __forceinline__ void sweep_residue(const float4v *quads, const float *tail,
-                                              LevelEntry mine, unsigned long long use,
+                                              LevelEntry mine, unsigned long long use, bool skip,
                                               float (&bq)[Q > 0 ? Q : 1][4], float (&bt)[T > 0 ? T : 1])
 {
-    // the usable entries of a residue are consecutive positions of the visiting order
-    int i = use ? __builtin_ctzll(use) : 0;
-    int n = __builtin_popcountll(use);
-    for (; n >= 2; n -= 2, i += 2) {
+    auto visit_two = [&](int i) {
         const int s0 = __builtin_amdgcn_readlane(mine.shift, i);
         const int s1 = __builtin_amdgcn_readlane(mine.shift, i + 1);
         float e0 = lane_value(mine.err, i);
@@ -822,8 +824,8 @@ __device__ __forceinline__ void sweep_residue(const float4v *quads, const float 
             for (int j = 0; j < T; ++j)
                 vmin3(bt[j], p0[j * kWave] + e0, p1[j * kWave] + e1);
         }
-    }
-    if (n) {
+    };
+    auto visit_one = [&](int i) {
         const int s0 = __builtin_amdgcn_readlane(mine.shift, i);
         float e0 = lane_value(mine.err, i);
         asm volatile("" : "+v"(e0));
@@ -844,17 +846,41 @@ __device__ __forceinline__ void sweep_residue(const float4v *quads, const float 
             for (int j = 0; j < T; ++j)
                 vmin(bt[j], p0[j * kWave] + e0);
         }
+    };
+    // the usable entries of a residue are consecutive positions of the visiting order
+    int i = use ? __builtin_ctzll(use) : 0;
+    int n = __builtin_popcountll(use);
+    if constexpr (kSplit) {
+        if (skip) {
+            i += 2;
+            n -= 2;
+        }
+        for (; n >= 2; n -= 4, i += 4)
+            visit_two(i);
+        if (n == 1)
+            visit_one(i);
+    } else {
+        for (; n >= 2; n -= 2, i += 2)
+            visit_two(i);
+        if (n)
+            visit_one(i);
     }
 }
 
 // One group of R chunks of one layer (D record, at most 64 levels): sweep with 128-bit reads,
 // store the record, write the new row values; the barrier protocol is fill_group's.
 // prev + t0 is 16-byte aligned (rows, aprons and chunk starts are multiples of four floats).
-template <int R, bool inplace>
+// kSplit (in place only): this wave has a twin in the other half of the workgroup with the same
+// group; the two visit alternate pairs of the layer's entries, the second half (`half` = 1)
+// leaves its minima in `part` (indexed like the row) before the barrier, and the first half
+// folds them into its own behind it.  min is exact and order-blind here, so the row is the one
+// a single wave would have computed.
+template <int R, bool inplace, bool kSplit>
 __device__ __forceinline__ void fill_group_quads(const float *prev, float *cur, float *rec,
                                                  LevelEntry first, int t0, int lane,
-                                                 Pending pending)
+                                                 Pending pending, int half, float *part)
 {
+    static_assert(!kSplit || inplace, "the halves meet at the in-place barrier");
     if constexpr (R == 0) {
         pending.settle();
         if (inplace)
@@ -881,13 +907,56 @@ __device__ __forceinline__ void fill_group_quads(const float *prev, float *cur, 
         // every wait for an LDS read in the sweep has to be a wait for ALL of them, and a wave
         // cannot start on the first quads while the later ones arrive.  Let them land first.
         __builtin_amdgcn_s_waitcnt(0xC07F);       // lgkmcnt(0), nothing else
-        sweep_residue<Q, T, 0>(quads, tail, first, use & __ballot(residue == 0), bq, bt);
-        sweep_residue<Q, T, 1>(quads, tail, first, use & __ballot(residue == 1), bq, bt);
-        sweep_residue<Q, T, 2>(quads, tail, first, use & __ballot(residue == 2), bq, bt);
-        sweep_residue<Q, T, 3>(quads, tail, first, use & __ballot(residue == 3), bq, bt);
+        const unsigned long long use0 = use & __ballot(residue == 0);
+        const unsigned long long use1 = use & __ballot(residue == 1);
+        const unsigned long long use2 = use & __ballot(residue == 2);
+        const unsigned long long use3 = use & __ballot(residue == 3);
+        // kSplit: the pairs of entries are numbered through the four runs; half h visits the
+        // pairs whose number is h mod 2, so both halves get every residue's kind of work
+        int turn = half;
+        sweep_residue<Q, T, 0, kSplit>(quads, tail, first, use0, turn & 1, bq, bt);
+        if constexpr (kSplit)
+            turn += (__builtin_popcountll(use0) + 1) >> 1;
+        sweep_residue<Q, T, 1, kSplit>(quads, tail, first, use1, turn & 1, bq, bt);
+        if constexpr (kSplit)
+            turn += (__builtin_popcountll(use1) + 1) >> 1;
+        sweep_residue<Q, T, 2, kSplit>(quads, tail, first, use2, turn & 1, bq, bt);
+        if constexpr (kSplit)
+            turn += (__builtin_popcountll(use2) + 1) >> 1;
+        sweep_residue<Q, T, 3, kSplit>(quads, tail, first, use3, turn & 1, bq, bt);
         pending.settle();
         const int tq = t0 + 4 * (lane - 1);       // this lane's first bucket of quad chunk 0
         const int tt = t0 + tail0 + lane;
+        if constexpr (kSplit) {
+            if (half) {
+                if (lane > 0) {
+#pragma unroll
+                    for (int j = 0; j < Q; ++j) {
+                        const float4v v = {bq[j][0], bq[j][1], bq[j][2], bq[j][3]};
+                        *reinterpret_cast<float4v *>(part + tq + j * kQuadChunk) = v;
+                    }
+                }
+#pragma unroll
+                for (int j = 0; j < T; ++j)
+                    part[tt + j * kWave] = bt[j];
+            }
+            __syncthreads();                      // every read of the row is done, `part` is written
+            if (half)
+                return;
+            if (lane > 0) {
+#pragma unroll
+                for (int j = 0; j < Q; ++j) {
+                    const float4v v = *reinterpret_cast<const float4v *>(part + tq + j * kQuadChunk);
+                    vmin(bq[j][0], v.x);
+                    vmin(bq[j][1], v.y);
+                    vmin(bq[j][2], v.z);
+                    vmin(bq[j][3], v.w);
+                }
+            }
+#pragma unroll
+            for (int j = 0; j < T; ++j)
+                vmin(bt[j], part[tt + j * kWave]);
+        }
         if (rec) {       // streamed: the record is not read again before the walk back
             if (lane > 0) {
 #pragma unroll
@@ -901,7 +970,7 @@ __device__ __forceinline__ void fill_group_quads(const float *prev, float *cur, 
             for (int j = 0; j < T; ++j)
                 __builtin_nontemporal_store(bt[j], &rec[tt + j * kWave]);
         }
-        if (inplace)
+        if (inplace && !kSplit)
             __syncthreads();
         if (lane > 0) {
 #pragma unroll
@@ -950,17 +1019,20 @@ __device__ __forceinline__ void fill_group(const float *prev, float *cur, uint8_
     }
 }
 
-template <bool kLevel, bool inplace, int kMax, bool kQuads>
+template <bool kLevel, bool inplace, int kMax, bool kQuads, bool kSplit = false>
 __device__ __forceinline__ void fill_group_n(int r, const float *prev, float *cur, uint8_t *choice,
                                              float *rec, LevelEntry first, LayerTable tl,
-                                             ErrRow er, int s8, int t0, int lane, Pending pending)
+                                             ErrRow er, int s8, int t0, int lane, Pending pending,
+                                             int half = 0, float *part = nullptr)
 {
+    static_assert(!kSplit || kQuads, "only the 128-bit sweep splits a layer's entries");
     switch (r) {
 #define SPDY_CASE(RR)                                                                          \
     case RR:                                                                                   \
         if constexpr (RR <= kMax) {                                                            \
             if constexpr (kQuads)                                                              \
-                fill_group_quads<RR, inplace>(prev, cur, rec, first, t0, lane, pending);       \
+                fill_group_quads<RR, inplace, kSplit>(prev, cur, rec, first, t0, lane,         \
+                                                      pending, half, part);                    \
             else                                                                               \
                 fill_group<RR, kLevel, inplace>(prev, cur, choice, rec, first, tl, er, s8, t0, \
                                                 lane, pending);                                \
@@ -1032,9 +1104,18 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 //              plain instantiation ignores `blocks`
 //   kTurns   : the workgroups that share a compute unit take turns at the instruction priority
 //              (see the layer loop); `units` is the number of compute units
+//   kSplit   : launched with twice the waves the plan was made for (D record, in place, S <= 64,
+//              no more candidates than compute units, so a workgroup has its unit to itself and
+//              one wave per SIMD and candidate issues too little).  Wave w of the second half is
+//              the twin of wave w of the first: same team, same chunks, the other pairs of each
+//              layer's entries (see fill_group_quads).  The second half only sweeps; tables,
+//              record, row and the final argmin are the first half's.  The partial rows of the
+//              second half lie in LDS behind the smaller allocation (the launch gets twice that).
 // `pitch` is the record's row pitch (elements per (k, l) row).
-template <bool kLevel, int kPath, bool kNarrow, bool kBlocks, bool kTurns = false>
-__global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void dp_fill(
+template <bool kLevel, int kPath, bool kNarrow, bool kBlocks, bool kTurns = false,
+          bool kSplit = false>
+__global__ __launch_bounds__(fill_waves<kLevel>() * (kSplit ? 2 : 1) * kWave, kLevel ? 8 : 4)
+void dp_fill(
     ErrSource src, const int32_t *__restrict__ meta, LevelTables tables, int units, int K, int L,
     int S, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
     float *__restrict__ rows, int32_t *__restrict__ tstar, float *__restrict__ cost, Resume resume,
@@ -1048,6 +1129,8 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     __shared__ __attribute__((aligned(8))) float s_entries[2][kMaxFillWaves][kWave];
     constexpr bool kLds = kPath != 0, inplace = kPath == 1;
     constexpr bool kQuads = !kLevel && kNarrow;  // the D-record sweep with 128-bit LDS reads
+    static_assert(!kSplit || (kQuads && kPath == 1 && !kBlocks && !kTurns),
+                  "the split launch is the plain in-place D-record fill");
     if (meta[kMetaPath] != kPath)
         return;                                  // another launch does the work
     const int bp = meta[kMetaBudget];
@@ -1064,7 +1147,14 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
         return;                                  // the first ceil(K / teams) workgroups suffice
     const int row = meta[kMetaRow];
     const int lane = tid & (kWave - 1);
-    const int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    int wave = __builtin_amdgcn_readfirstlane(tid / kWave);
+    int half = 0;                                // kSplit: 1 for the twins of the planned waves
+    if constexpr (kSplit) {
+        const int planned = nthreads / (2 * kWave);
+        half = wave >= planned ? 1 : 0;
+        wave -= half * planned;
+    }
+    const bool lead = half == 0;
     const int team = wave / tw;
     const int wv = wave - team * tw;             // this wave's index in its team
     // Which share of the row this wave sweeps.  The low chunks of a row cost less than the high
@@ -1103,7 +1193,7 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     // a candidate that shares its first l0 layers with the incumbent starts from the incumbent's
     // row l0 - 1, placed where layer l0 reads its previous row
     const int l0 = active ? resume.start(k, L) : 0;
-    if (l0 > 0) {
+    if (l0 > 0 && lead) {
         float *dst = (l0 & 1) ? buf1 : buf0;
         const float *from = resume.inc_rec + (size_t)(l0 - 1) * pitch;
         const int n = nact[l0 - 1] * kWave;
@@ -1144,7 +1234,10 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     const int s8 = tables.s8;
     // S <= 64: the first wave of a team prepares, for the next layer, the team's table of merged
     // errors (D record) or the set of levels worth visiting (level record)
-    const bool producer = kNarrow && share == 0 && team < teams;
+    const bool producer = kNarrow && share == 0 && team < teams && lead;
+    // kSplit: where the twins of this wave's team leave their minima
+    float *part = kSplit ? lds + kLdsHalf / (int)sizeof(float) + (size_t)(team < teams ? team : 0) * row
+                         : nullptr;
     unsigned long long *keep =
         reinterpret_cast<unsigned long long *>(&s_entries[0][0][0]) + (team < teams ? team : 0);
     float *table = &s_entries[0][team < teams ? team : 0][0];
@@ -1239,8 +1332,9 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
         constexpr int kMax = group_limit<kLevel, kTurns>();
         const Pending pending{&next_fetch, &next_first};
         if constexpr (inplace) {                 // c_end - c <= kMax by construction
-            fill_group_n<kLevel, true, kMax, kQuads>(min(c_end - c, kMax), prev, cur, choice_l, drec_l, first,
-                                       tl, er, s8, c * kWave, lane, pending);
+            fill_group_n<kLevel, true, kMax, kQuads, kSplit>(min(c_end - c, kMax), prev, cur,
+                                                             choice_l, drec_l, first, tl, er, s8,
+                                                             c * kWave, lane, pending, half, part);
         } else {
             // Rows in global memory: the row is computed in tiles of at most kMax chunks per
             // wave, and the part of the previous row a tile reads (the tile itself and the
@@ -1321,7 +1415,7 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
     const float *last = (L & 1) ? buf1 : buf0;
     float bv = __builtin_inff();
     int bt = INT32_MAX;
-    if (active)
+    if (active && lead)
         for (int t = wv * kWave + lane; t <= bp; t += tw * kWave)
             argmin_merge(bv, bt, last[t], t);
 #pragma unroll
@@ -1330,12 +1424,12 @@ __global__ __launch_bounds__(fill_waves<kLevel>() * kWave, kLevel ? 8 : 4) void 
         const int ot = __shfl_down(bt, off, kWave);
         argmin_merge(bv, bt, ov, ot);
     }
-    if (lane == 0) {
+    if (lane == 0 && lead) {
         s_best[wave] = bv;
         s_time[wave] = bt;
     }
     __syncthreads();
-    if (active && wv == 0 && lane == 0) {
+    if (active && lead && wv == 0 && lane == 0) {
         for (int w = 1; w < tw; ++w)
             argmin_merge(bv, bt, s_best[wave + w], s_time[wave + w]);
         write_result(bv, bt, k, tstar, cost);
@@ -1672,6 +1766,23 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     const bool in_memory = need > (size_t)kLdsBytes;      // implies lay.may_spill
     auto in_place = turns ? dp_fill<kLevel, 1, kNarrow, kBlocks, true>
                           : dp_fill<kLevel, 1, kNarrow, kBlocks, false>;
+    // A candidate that has a compute unit to itself gets twice the waves (the second half takes
+    // every other pair of each layer's entries and needs a second row in LDS for its minima).
+    constexpr bool can_split = !kLevel && kNarrow && !kBlocks;
+    const bool split = can_split && K <= units;
+    int place_threads = waves * kWave, place_lds = lds_small;
+    if constexpr (can_split) {
+        if (split) {
+            in_place = dp_fill<kLevel, 1, kNarrow, kBlocks, false, true>;
+            place_threads *= 2;
+            place_lds *= 2;
+            static_assert(2 * kLdsHalf <= kLdsBytes, "two half allocations fit one workgroup");
+            if (hipFuncSetAttribute(reinterpret_cast<const void *>(in_place),
+                                    hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    kLdsBytes) != hipSuccess)
+                return SPDY_DP_ERR_LAUNCH;
+        }
+    }
     auto two_rows = dp_fill<kLevel, 2, kNarrow, kBlocks>;
     auto in_global = dp_fill<kLevel, 0, kNarrow, kBlocks>;
     // always the same limit, so that calls from several host threads cannot undo each other's
@@ -1691,10 +1802,10 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     if (!(kBlocks && blocks.pass == 1))          // the block passes reuse pass 0's tables
         hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, K, 2 * units, L, S, s8,
                            B, waves, max_group, lds_small, lds_large, lds_stage,
-                           kLevel ? 0 : (kNarrow ? 2 : 1), meta,
+                           kLevel ? 0 : (kNarrow ? 2 : 1), split ? 1 : 0, meta,
                            shifts, order, start, entry);
     const LevelTables tables{shifts, order, start, entry, s8};
-    hipLaunchKernelGGL(in_place, dim3(K), dim3(waves * kWave), lds_small, q, src, meta, tables,
+    hipLaunchKernelGGL(in_place, dim3(K), dim3(place_threads), place_lds, q, src, meta, tables,
                        units, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     if (lds_large)
         hipLaunchKernelGGL(two_rows, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, tables,

@@ -92,7 +92,11 @@ def check_tables(dp, tau, err_k, B, ws, k, K):
     # a workgroup can hold all its chunks in registers; otherwise two rows (with their aprons)
     # alternate in LDS if the larger launch has room for them, else they live in global memory.
     path, team_waves, teams, inplace = (int(x) for x in meta[3:7])
-    waves, max_group, lds_small, lds_large, halo = (int(x) for x in meta[8:13])
+    waves, max_group, lds_small, lds_large, halo, split = (int(x) for x in meta[8:14])
+    # a D-record candidate with at most 64 levels that has a compute unit to itself is swept by
+    # twice the planned waves (the plan itself is the same)
+    units = torch.cuda.get_device_properties(0).multi_processor_count
+    assert split == int(K <= units and lay["variant"] == 0 and S <= 64)
     chunks = int(meta[2]) // 64
     row_bytes = (int(meta[2]) + halo) * 4
     assert inplace == int(chunks <= waves * max_group)
@@ -208,21 +212,29 @@ def test_every_group_size_of_the_sweep(dp):
     to the most a wave keeps in registers (the sweep is specialised per size: so many chunks
     read four buckets per lane, so many one), with one candidate per workgroup (eight waves on a
     row) and with several (teams of fewer waves), shifts of every residue mod 4 and layers whose
-    shifts all share one residue."""
+    shifts all share one residue.  Each of the three in-place launches sees every size: the one
+    for candidates that have a compute unit to themselves (two waves per share of the row), the
+    one for one or two rounds of workgroups, and the one for long batches."""
     rng = np.random.default_rng(4242)
     dev = torch.device("cuda:0")
     lay = dp.spdy_dp_workspace_layout(1, 2, 2, 64, dp.spdy_dp_workspace_bytes(1, 2, 2, 64))
-    seen = set()
-    for K in (1, 600):
-        for chunks in list(range(1, 17)) + list(range(17, 8 * 28 + 1, 5)) + [8 * 28]:
+    units = torch.cuda.get_device_properties(0).multi_processor_count
+    long_batch = 4 * units + 70
+    seen = {1: set(), 600: set(), long_batch: set()}
+    for K in seen:
+        sizes = list(range(1, 17)) + list(range(17, 8 * 28 + 1, 5)) + [8 * 28]
+        if K == long_batch:       # every share from 1 to 26 chunks once, and two ragged rows
+            sizes = [8 * r for r in range(1, 27)] + [13, 203]
+        for chunks in sizes:
             B = 64 * chunks - int(rng.integers(1, 64))          # reduced row of `chunks` chunks
             L, S = 3, 7
             tau = rng.integers(0, max(2, B // 3), size=(L, S)).astype(np.int32)
             tau[:, 0] = 0                                       # m_l = 0: the row is not reduced
+            tau[:, 1] = (B + 2) // 3 + 4                        # the last row is reached in full
             if chunks % 3 == 0:
                 tau[1] = tau[1] // 4 * 4 + int(rng.integers(0, 4))   # one residue for a layer
                 tau[1, 0] = 0
-            kk = K if chunks <= 40 or chunks >= 219 else min(K, 3)
+            kk = K
             err = rng.integers(0, 5, size=(kk, L, S)).astype(np.float32) if chunks % 2 else \
                 rng.random((kk, L, S), dtype=np.float32)
             p_ref, c_ref = oracle.solve_ref(tau, err, B, threads=CPU_THREADS)
@@ -234,8 +246,10 @@ def test_every_group_size_of_the_sweep(dp):
             meta = ws[off:off + 4 * (H + (3 + plan) * L)].cpu().numpy().view(np.int32)
             team_waves = int(meta[4])
             shares = meta[H + 2 * L:H + (2 + plan) * L].reshape(L, plan)[:, :team_waves + 1]
-            seen.update(int(x) for x in np.diff(shares, axis=1).ravel())
-    assert set(range(1, 29)) <= seen, sorted(set(range(1, 29)) - seen)
+            seen[K].update(int(x) for x in np.diff(shares, axis=1).ravel())
+            assert int(meta[13]) == int(kk <= units)
+    for K, most in ((1, 26), (600, 28), (long_batch, 26)):
+        assert set(range(1, most + 1)) <= seen[K], (K, sorted(set(range(1, most + 1)) - seen[K]))
 
 
 def test_infeasible_and_mixed_batches(dp):
