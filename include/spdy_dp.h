@@ -205,7 +205,9 @@ int spdy_dp_solve_checkpointed(const int32_t *tau, const float *err, int K, int 
  *          [6] 1 if rows are updated in place; and what that choice was made from: [7] bytes of
  *          LDS for the windows of launch 0, [8] waves per workgroup, [9] most 64-bucket chunks a
  *          wave keeps in registers, [10] / [11] dynamic LDS bytes of launches 1 / 2 (0: not
- *          enqueued), [12] floats of +inf apron left of a row.  Per-layer arrays follow the
+ *          enqueued), [12] floats of +inf apron left of a row, [13] 1 if launch 1 ran with
+ *          twice the waves of [8], the second half dividing each layer's levels with the first
+ *          (D record, S <= 64, no more candidates than compute units).  Per-layer arrays follow the
  *          out[6] header words: m_l at [out[6] + l], the number of computed 64-bucket chunks of
  *          layer l at [out[6] + L + l], the largest usable shift of layer l at
  *          [out[6] + (2 + out[7]) L + l]
