@@ -89,13 +89,16 @@ static_assert(kInPlaceFits, "path 1 must be exactly the in-place case");
 constexpr int kBatch = 8;                 // level tables are padded to a multiple of this
 constexpr unsigned kNoLevel = 0xFF;
 constexpr size_t kAlign = 256;
-constexpr int kMetaHeader = 16;      // int32 words before the per-layer arrays
+constexpr int kMetaHeader = 20;      // int32 words before the per-layer arrays
 // meta: header | m_l [L] | chunks of row l [L] | chunk boundaries of the team waves [L][stride]
 //       | largest usable shift of layer l [L]
 constexpr int kRangeStride = kMaxFillWaves + 1;
 
 // kMetaPath: 0 = rows in global memory, 1 / 2 = rows in LDS, fill kernel launched with the
-// smaller / larger LDS allocation.  kMetaTeamWaves x kMetaTeams <= waves of a fill workgroup.
+// smaller / larger LDS allocation, 3 = one row in LDS updated in place by a workgroup of twice
+// the waves that has a compute unit's LDS to itself (D record; rows too long for path 1),
+// 4 = rows in global memory, a workgroup of twice the waves (D record).
+// kMetaTeamWaves x kMetaTeams <= waves of a fill workgroup.
 // kMetaInPlace: every wave of a team holds all its chunks of a row in registers, so one row per
 // candidate suffices (written back between two barriers); otherwise two rows alternate.
 enum MetaWord {
@@ -108,7 +111,11 @@ enum MetaWord {
     kMetaLdsSmall = 10, // dynamic LDS bytes of the in-place launch
     kMetaLdsLarge = 11, // dynamic LDS bytes of the two-row launch (0: not enqueued)
     kMetaHalo = 12,     // floats of the +inf apron left of a row
-    kMetaSplit = 13     // 1: the in-place launch has twice kMetaWaves waves (see dp_fill, kSplit)
+    kMetaSplit = 13,    // 1: the in-place launch has twice kMetaWaves waves (see dp_fill, kSplit)
+    kMetaWideWaves = 14, // waves of the wide in-place launch (0: not enqueued)
+    kMetaWideGroup = 15, // most chunks one of its waves keeps in registers
+    kMetaLdsWide = 16,   // its dynamic LDS bytes
+    kMetaGlobalWaves = 17 // waves of the global-row launch
 };
 
 enum Variant { kValueRecord = 0, kLevelRecord = 1 };
@@ -231,7 +238,8 @@ __device__ __forceinline__ long long block_scan_256(long long v, long long *part
 // of layers.
 __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots, int L, int S,
                                int B, int waves, int max_group, int lds_small, int lds_large,
-                               int lds_stage, int split, int32_t *__restrict__ meta)
+                               int lds_stage, int split, int wide_waves, int wide_group,
+                               int lds_wide, int global_waves, int32_t *__restrict__ meta)
 {
     __shared__ long long s_sum[8];
     __shared__ int s_budget, s_team_waves;
@@ -265,16 +273,27 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots
         meta[kMetaMinTime] = M > INT32_MAX ? INT32_MAX : (int)M;
         meta[kMetaRow] = rowp;
         int path = 1, teams = 1, inplace = 0;     // an infeasible table is reported by path 1
+        int plan_waves = waves;                   // waves of the launch that does the work
         if (bp >= 0) {
             const long long one_row = ((long long)rowp + kHalo) * (long long)sizeof(float);
             const int want = (rowp / kWave + max_group - 1) / max_group;   // waves per candidate
             inplace = want <= waves ? 1 : 0;
             // a row updated in place always fits lds_small (kInPlaceFits), so path 1 is exactly
-            // the in-place case
+            // the in-place case of a workgroup of `waves` waves
             const long long team_lds = inplace ? one_row : 2 * one_row;
             const int lds = lds_small;
             path = inplace ? 1 : (team_lds <= lds_large ? 2 : 0);
-            if (inplace) {
+            // a longer row that the waves of the wide launch can still hold in registers, and
+            // that fits its LDS, is updated in place there
+            if (!inplace && wide_waves > 0 &&
+                (rowp / kWave + wide_group - 1) / wide_group <= wide_waves && one_row <= lds_wide) {
+                path = 3;
+                inplace = 1;
+                plan_waves = wide_waves;
+            } else if (path == 0 && global_waves > waves) {
+                path = 4;                         // the global-row launch of twice the waves
+                plan_waves = global_waves;
+            } else if (inplace) {
                 // as many candidates per workgroup as keeps every wave at <= max_group chunks
                 teams = waves / want;
                 const long long fit = lds / team_lds;
@@ -289,7 +308,7 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots
         }
         meta[kMetaPath] = path;
         meta[kMetaTeams] = teams;
-        meta[kMetaTeamWaves] = waves / teams;
+        meta[kMetaTeamWaves] = plan_waves / teams;
         meta[kMetaInPlace] = inplace;
         meta[kMetaStage] = lds_stage;
         meta[kMetaWaves] = waves;
@@ -298,8 +317,12 @@ __device__ void prepare_budget(const int32_t *__restrict__ tau, int K, int slots
         meta[kMetaLdsLarge] = lds_large;
         meta[kMetaHalo] = kHalo;
         meta[kMetaSplit] = split;
+        meta[kMetaWideWaves] = wide_waves;
+        meta[kMetaWideGroup] = wide_group;
+        meta[kMetaLdsWide] = lds_wide;
+        meta[kMetaGlobalWaves] = global_waves;
         s_budget = bp;
-        s_team_waves = waves / teams;
+        s_team_waves = plan_waves / teams;
     }
     __syncthreads();
     const int bp = s_budget;
@@ -434,7 +457,8 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
                                                   int slots, int L, int S,
                                                   int s8, int B, int waves, int max_group,
                                                   int lds_small, int lds_large, int lds_stage,
-                                                  int sorted, int split,
+                                                  int sorted, int split, int wide_waves,
+                                                  int wide_group, int lds_wide, int global_waves,
                                                   int32_t *__restrict__ meta,
                                                   int32_t *__restrict__ shifts,
                                                   int32_t *__restrict__ order,
@@ -443,7 +467,7 @@ __global__ __launch_bounds__(256) void dp_prepare(const int32_t *__restrict__ ta
 {
     if (blockIdx.x == 0)
         prepare_budget(tau, K, slots, L, S, B, waves, max_group, lds_small, lds_large, lds_stage,
-                       split, meta);
+                       split, wide_waves, wide_group, lds_wide, global_waves, meta);
     else
         prepare_order(tau, blockIdx.x - 1, S, s8, sorted, shifts, order, start, entry_of);
 }
@@ -1095,8 +1119,14 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 //              the same row, barrier.  2: two rows in LDS alternate, one barrier per layer.
 //              0: two rows of kHalo + pitch floats in `rows` in global memory, one candidate per
 //              workgroup.  (A row that can be updated in place always fits the smaller LDS
-//              allocation and two longer ones never do, so path 1 is exactly the in-place case;
-//              each instantiation holds only its own way of stepping through a layer.)
+//              allocation and two longer ones never do, so path 1 is exactly the in-place case
+//              of a workgroup of the usual size; each instantiation holds only its own way of
+//              stepping through a layer.)
+//              3 (D record): path 1's code in a workgroup of twice the waves with up to a whole
+//              compute unit's LDS: rows of up to twice path 1's length are still updated in
+//              place (one candidate per workgroup, one workgroup per compute unit at a time).
+//              4 (D record): path 0's code in a workgroup of twice the waves with a whole compute
+//              unit's LDS for the window (its tiles are twice as long).
 //   kNarrow  : S <= 64, one lane per level: the next layer's table is loaded without dependent
 //              loads while a layer is swept (a separate instantiation, so that the waits of the
 //              two ways of loading do not meet in one control-flow join)
@@ -1114,7 +1144,8 @@ __device__ __forceinline__ void write_result(float bv, int bt, int k, int32_t *t
 // `pitch` is the record's row pitch (elements per (k, l) row).
 template <bool kLevel, int kPath, bool kNarrow, bool kBlocks, bool kTurns = false,
           bool kSplit = false>
-__global__ __launch_bounds__(fill_waves<kLevel>() * (kSplit ? 2 : 1) * kWave, kLevel ? 8 : 4)
+__global__ __launch_bounds__(fill_waves<kLevel>() * (kSplit || kPath >= 3 ? 2 : 1) * kWave,
+                             kLevel ? 8 : 4)
 void dp_fill(
     ErrSource src, const int32_t *__restrict__ meta, LevelTables tables, int units, int K, int L,
     int S, int pitch, uint8_t *__restrict__ choice, float *__restrict__ drec,
@@ -1127,7 +1158,10 @@ void dp_fill(
     // per team and for two layers: merged errors (D record), or in the same storage one 64-bit
     // set of levels to visit (level record)
     __shared__ __attribute__((aligned(8))) float s_entries[2][kMaxFillWaves][kWave];
-    constexpr bool kLds = kPath != 0, inplace = kPath == 1;
+    constexpr bool kGlobal = kPath == 0 || kPath == 4;     // rows in global memory
+    constexpr bool kLds = !kGlobal, inplace = kPath == 1 || kPath == 3;
+    static_assert(kPath < 3 || (!kLevel && !kBlocks && !kTurns && !kSplit),
+                  "the launches of twice the waves are plain D-record fills");
     constexpr bool kQuads = !kLevel && kNarrow;  // the D-record sweep with 128-bit LDS reads
     static_assert(!kSplit || (kQuads && kPath == 1 && !kBlocks && !kTurns),
                   "the split launch is the plain in-place D-record fill");
@@ -1140,7 +1174,7 @@ void dp_fill(
             write_result(__builtin_inff(), 0, blockIdx.x, tstar, cost);
         return;
     }
-    tables.limit = kPath == 0 ? bp : INT32_MAX;  // only the tiles of path 0 depend on it
+    tables.limit = kGlobal ? bp : INT32_MAX;     // only the tiles of global rows depend on it
     const int teams = meta[kMetaTeams];
     const int tw = meta[kMetaTeamWaves];
     if ((long long)blockIdx.x * teams >= K)
@@ -1343,12 +1377,12 @@ void dp_fill(
             // wave takes the same number of trips.  A layer whose largest shift leaves no room
             // for a tile is swept from global memory.
             int tile = 0, span = 0;
-            if constexpr (kPath == 0) {
+            if constexpr (kGlobal) {
                 span = meta[kMetaHeader + (2 + (size_t)kRangeStride) * L + l];
                 tile = (meta[kMetaStage] / (int)sizeof(float) - span - 8) / kWave / tw * tw;
                 tile = min(tile, tw * kMax);
             }
-            if (kPath == 0 && tile >= tw) {
+            if (kGlobal && tile >= tw) {
                 const int n_l = (active && l >= l0) ? nact[l] : 0;
                 if (n_l == 0)
                     pending.settle();
@@ -1759,11 +1793,24 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     const int waves = nchunks < fill_waves<kLevel>() ? nchunks : fill_waves<kLevel>();
     const int max_group = turns ? group_limit<kLevel, true>() : group_limit<kLevel, false>();
     const size_t row_bytes = (lay.row + kHalo) * sizeof(float);
-    const size_t need = (long long)nchunks <= (long long)waves * max_group ? row_bytes : 2 * row_bytes;
+    const bool beyond_place = (long long)nchunks > (long long)waves * max_group;
+    const size_t need = beyond_place ? 2 * row_bytes : row_bytes;
     const int lds_small = kLdsHalf;
-    const int lds_large = need <= (size_t)kLdsHalf ? 0
+    // D record: a row too long for the in-place launch may still be updated in place by a
+    // workgroup of twice the waves that takes up to a whole compute unit's LDS (every length the
+    // two-row launch could take is covered by it, so that launch is not enqueued then).
+    constexpr bool can_widen = !kLevel && !kBlocks;
+    const bool wide = can_widen && beyond_place;
+    const int wide_waves = wide ? 2 * fill_waves<kLevel>() : 0;
+    const int wide_group = group_limit<kLevel, false>();
+    const int lds_wide = wide ? (int)(row_bytes < (size_t)kLdsBytes ? row_bytes : kLdsBytes) : 0;
+    const int lds_large = (need <= (size_t)kLdsHalf || wide) ? 0
                           : (need <= (size_t)kLdsBytes ? (int)need : kLdsBytes);
-    const bool in_memory = need > (size_t)kLdsBytes;      // implies lay.may_spill
+    // whether the full budget's row may have to live in global memory (implies lay.may_spill)
+    const bool in_memory =
+        wide ? ((long long)nchunks > (long long)wide_waves * wide_group ||
+                row_bytes > (size_t)kLdsBytes)
+             : need > (size_t)kLdsBytes;
     auto in_place = turns ? dp_fill<kLevel, 1, kNarrow, kBlocks, true>
                           : dp_fill<kLevel, 1, kNarrow, kBlocks, false>;
     // A candidate that has a compute unit to itself gets twice the waves (the second half takes
@@ -1785,15 +1832,29 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     }
     auto two_rows = dp_fill<kLevel, 2, kNarrow, kBlocks>;
     auto in_global = dp_fill<kLevel, 0, kNarrow, kBlocks>;
+    auto wide_place = dp_fill<kLevel, can_widen ? 3 : 1, kNarrow, kBlocks>;   // (3 when it exists)
+    // The D record's global-row launch also has twice the waves (one workgroup per compute unit
+    // with all of its LDS for the window; measured against two workgroups of the usual size with
+    // half the LDS each: 11 % faster on a batch of four candidates per unit).
+    const bool wide_global = can_widen && waves == fill_waves<kLevel>();
+    const int global_waves = wide_global ? 2 * waves : waves;
+    if constexpr (can_widen) {
+        if (wide_global)
+            in_global = dp_fill<kLevel, 4, kNarrow, kBlocks>;
+    }
+    if (wide &&
+        hipFuncSetAttribute(reinterpret_cast<const void *>(wide_place),
+                            hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
+        return SPDY_DP_ERR_LAUNCH;
     // always the same limit, so that calls from several host threads cannot undo each other's
     if (lds_large &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(two_rows),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
         return SPDY_DP_ERR_LAUNCH;
     // The global-row launch stages its tiles' windows in LDS: all of it with one workgroup per
-    // compute unit, half of it when there are candidates for two (one sweeps while the other
-    // copies).
-    const int lds_stage = K > units ? kLdsHalf : kLdsBytes;
+    // compute unit; workgroups of the usual size take half of it when there are candidates for
+    // two per unit (one sweeps while the other copies).
+    const int lds_stage = (K > units && !wide_global) ? kLdsHalf : kLdsBytes;
     if (in_memory &&
         hipFuncSetAttribute(reinterpret_cast<const void *>(in_global),
                             hipFuncAttributeMaxDynamicSharedMemorySize, kLdsBytes) != hipSuccess)
@@ -1802,16 +1863,20 @@ int launch_fill(const Layout &lay, const int32_t *tau, ErrSource src, Resume res
     if (!(kBlocks && blocks.pass == 1))          // the block passes reuse pass 0's tables
         hipLaunchKernelGGL(dp_prepare, dim3(L + 1), dim3(256), 0, q, tau, K, 2 * units, L, S, s8,
                            B, waves, max_group, lds_small, lds_large, lds_stage,
-                           kLevel ? 0 : (kNarrow ? 2 : 1), split ? 1 : 0, meta,
-                           shifts, order, start, entry);
+                           kLevel ? 0 : (kNarrow ? 2 : 1), split ? 1 : 0, wide_waves, wide_group,
+                           lds_wide, global_waves, meta, shifts, order, start, entry);
     const LevelTables tables{shifts, order, start, entry, s8};
     hipLaunchKernelGGL(in_place, dim3(K), dim3(place_threads), place_lds, q, src, meta, tables,
                        units, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
+    if (wide)
+        hipLaunchKernelGGL(wide_place, dim3(K), dim3(wide_waves * kWave), lds_wide, q, src, meta,
+                           tables, units, K, L, S, pitch, choice, drec, rows, tstar, cost, resume,
+                           blocks);
     if (lds_large)
         hipLaunchKernelGGL(two_rows, dim3(K), dim3(waves * kWave), lds_large, q, src, meta, tables,
                            units, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     if (in_memory)
-        hipLaunchKernelGGL(in_global, dim3(K), dim3(waves * kWave), lds_stage, q, src, meta, tables,
+        hipLaunchKernelGGL(in_global, dim3(K), dim3(global_waves * kWave), lds_stage, q, src, meta, tables,
                            units, K, L, S, pitch, choice, drec, rows, tstar, cost, resume, blocks);
     return launch_status();
 }

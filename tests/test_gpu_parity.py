@@ -89,25 +89,36 @@ def check_tables(dp, tau, err_k, B, ws, k, K):
     rec = rec.view(np.float32 if esize == 4 else np.uint8).reshape(rows, pitch)
     # Which launch did the work must follow from what the header says the choice was made from
     # (no tuning constant is repeated here): a row is updated in place exactly when the waves of
-    # a workgroup can hold all its chunks in registers; otherwise two rows (with their aprons)
-    # alternate in LDS if the larger launch has room for them, else they live in global memory.
+    # a workgroup can hold all its chunks in registers (the usual workgroup, or, for the D
+    # record, the wide one with a compute unit's LDS to itself); otherwise two rows (with their
+    # aprons) alternate in LDS if the larger launch has room for them, else they live in global
+    # memory.
     path, team_waves, teams, inplace = (int(x) for x in meta[3:7])
-    waves, max_group, lds_small, lds_large, halo, split = (int(x) for x in meta[8:14])
+    waves, max_group, lds_small, lds_large, halo, split, wide_waves, wide_group, lds_wide, \
+        global_waves = (int(x) for x in meta[8:18])
     # a D-record candidate with at most 64 levels that has a compute unit to itself is swept by
     # twice the planned waves (the plan itself is the same)
     units = torch.cuda.get_device_properties(0).multi_processor_count
     assert split == int(K <= units and lay["variant"] == 0 and S <= 64)
     chunks = int(meta[2]) // 64
     row_bytes = (int(meta[2]) + halo) * 4
-    assert inplace == int(chunks <= waves * max_group)
-    if inplace:
+    fits_place = chunks <= waves * max_group
+    fits_wide = wide_waves > 0 and chunks <= wide_waves * wide_group and row_bytes <= lds_wide
+    assert inplace == int(fits_place or fits_wide)
+    assert wide_waves == 0 or (lay["variant"] == 0 and lds_large == 0)
+    if fits_place:
         assert path == 1 and row_bytes * teams <= lds_small
         assert 1 <= teams and teams * team_waves <= waves
         assert chunks <= team_waves * max_group         # a team's waves hold the whole row
+    elif fits_wide:
+        assert path == 3 and teams == 1 and team_waves == wide_waves
+        max_group = wide_group
     elif 2 * row_bytes <= lds_large:
         assert path == 2 and teams == 1
-    else:
-        assert path == 0 and teams == 1
+    else:       # rows in global memory; twice the waves for the D record
+        assert global_waves == (2 * waves if lay["variant"] == 0 else waves)
+        assert path == (4 if global_waves > waves else 0) and teams == 1
+        assert team_waves == global_waves
     # every wave's share of every row fits its registers when the row is updated in place
     plan_rows = meta[H + 2 * L:H + (2 + plan) * L].reshape(L, plan)[:, :team_waves + 1]
     assert (plan_rows[:, 0] == 0).all() and (plan_rows[:, team_waves] == nact).all()
@@ -164,10 +175,14 @@ EDGE_SHAPES = [
     # K, L, S, B  (B + 1 deliberately not a multiple of 64 in most; several chunks per wave)
     (3, 1, 1, 0), (2, 1, 5, 7), (4, 5, 1, 100), (5, 6, 7, 63), (5, 6, 7, 64), (3, 9, 12, 1000),
     (7, 12, 33, 2500), (2, 4, 255, 700), (3, 17, 40, 10000), (2, 20, 16, 16384),
-    (2, 7, 9, 17599), (2, 6, 10, 17600),             # around the largest rows that fit LDS
-    (3, 6, 10, 20480), (2, 5, 12, 33000), (1, 4, 6, 70001),   # rows in global memory, tiles
+    (2, 7, 9, 17599), (2, 6, 10, 17600),             # around the largest rows two of which fit LDS
+    (3, 6, 10, 20480),                               # one row in LDS, twice the waves
+    (2, 5, 9, 26623), (2, 5, 9, 26624),              # around the longest row they keep in registers
+    (300, 3, 5, 22000),                              # ... with more candidates than compute units
+    (2, 5, 12, 33000), (1, 4, 6, 70001),             # rows in global memory, tiles
     (1, 2, 5, 70001),     # ... and shifts too long for a tile's window in LDS
-    (300, 3, 5, 22000),   # ... and two workgroups per compute unit with half-size windows
+    (300, 3, 5, 30000),   # ... and more candidates than compute units (level record: two
+                          # workgroups per unit with half-size windows)
     (2, 300, 3, 500),                                # more layers than prepare threads
     (2, 5, 64, 300), (2, 5, 65, 300), (3, 4, 129, 900),       # level-block boundaries
     (37, 4, 5, 200), (19, 3, 6, 1500),               # few candidates: one team per workgroup
@@ -579,9 +594,12 @@ def test_a_solve_captured_in_a_graph_replays_correctly(dp):
         assert_same(eager_p.cpu().numpy(), eager_c.cpu().numpy(), *want, f"eager {rep}")
 
 
-def test_a_solve_that_needs_the_larger_lds_launch_replays_from_a_graph(dp):
-    """Rows too long to be updated in place take the launch with the larger LDS allocation, whose
-    attribute is set by the call itself; that call, captured, must replay correctly too."""
+@pytest.mark.parametrize("compact, launch", [(False, 3), (True, 2)],
+                         ids=["d_record_wide_in_place", "level_record_two_rows"])
+def test_a_solve_that_needs_the_larger_lds_launch_replays_from_a_graph(dp, compact, launch):
+    """Rows too long for the usual in-place launch take a launch with a larger LDS allocation
+    (D record: the wide in-place one; level record: two alternating rows), whose attribute is
+    set by the call itself; that call, captured, must replay correctly too."""
     dev = torch.device("cuda:0")
     rng = np.random.default_rng(607)
     K, L, S, B = 3, 6, 10, 17000
@@ -591,14 +609,14 @@ def test_a_solve_that_needs_the_larger_lds_launch_replays_from_a_graph(dp):
     p_other, c_other = oracle.solve_ref(tau, other, B)
     tau_d = torch.from_numpy(tau).to(dev)
     err_d = torch.from_numpy(err).to(dev)
-    ws = dp.alloc_workspace(K, L, S, B, dev)
+    ws = dp.alloc_workspace(K, L, S, B, dev, compact=compact)
     profile = torch.empty((K, L), dtype=torch.int16, device=dev)
     cost = torch.empty((K,), dtype=torch.float32, device=dev)
     dp.spdy_dp_solve_batched(tau_d, err_d, B, profile, cost, ws)
     torch.cuda.synchronize()
     lay = dp.spdy_dp_workspace_layout(K, L, S, B, ws.numel())
     path = int(ws[lay["meta_offset"] + 12:lay["meta_offset"] + 16].cpu().numpy().view(np.int32)[0])
-    assert path == 2, "this shape is meant to take the two-row launch"
+    assert path == launch, "this shape is meant to take the launch with the larger allocation"
     assert_same(profile.cpu().numpy(), cost.cpu().numpy(), p_ref, c_ref, "eager")
     graph = torch.cuda.CUDAGraph()
     stream = torch.cuda.Stream()

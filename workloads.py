@@ -66,14 +66,18 @@ CONFIGS = {
     "rn50_params_k1024": Config("rn50_params_k1024", K=1024, L=54, S=40, B=10000, q=0.9,
                                 speedup=4.0, dense="rn50_params", sigma=0.0),
     # Not benchmark lines: tables that take the other launches of the fill, for profiling them.
-    # The stress recipe with looser speed-up targets leaves longer reduced rows: two rows in LDS
-    # (X = 3.8, about 15.5 K reduced buckets) and rows in global memory (X = 3.0, about 26 K);
-    # the ResNet-50 recipe with ten times the buckets (global rows, two workgroups per compute
-    # unit); and the ResNet-50 recipe with 128 levels (the instantiations for S > 64).
+    # The stress recipe with looser speed-up targets leaves longer reduced rows: X = 3.8 about
+    # 15.5 K reduced buckets and X = 3.0 about 26 K (one row in LDS updated in place by a
+    # workgroup of twice the waves; the level record takes two rows in LDS or global rows there),
+    # X = 2.5 about 32.6 K (rows in global memory, one workgroup per compute unit); the ResNet-50
+    # recipe with ten times the buckets (global rows, two workgroups per compute unit); and the
+    # ResNet-50 recipe with 128 levels (the instantiations for S > 64).
     "stress_x38_k256": Config("stress_x38_k256", K=256, L=200, S=64, B=65536, q=0.93,
                               speedup=3.8, dense="lognormal", sigma=1.0),
     "stress_x30_k256": Config("stress_x30_k256", K=256, L=200, S=64, B=65536, q=0.93,
                               speedup=3.0, dense="lognormal", sigma=1.0),
+    "stress_x25_k256": Config("stress_x25_k256", K=256, L=200, S=64, B=65536, q=0.93,
+                              speedup=2.5, dense="lognormal", sigma=1.0),
     "rn50_b100k_k1024": Config("rn50_b100k_k1024", K=1024, L=54, S=40, B=100000, q=0.9,
                                speedup=2.5, dense="lognormal", sigma=0.8),
     "rn50_s128_k1024": Config("rn50_s128_k1024", K=1024, L=54, S=128, B=10000, q=0.97,
