@@ -201,13 +201,16 @@ int spdy_dp_solve_checkpointed(const int32_t *tau, const float *err, int K, int 
  *   out[1] byte offset of the int32 header: [0] B - M (or -1 if M > B: nobody is feasible),
  *          [1] M, [2] reduced row length (B - M + 1 padded to 64), [3] which launch of the fill
  *          did the work: 0 rows in global memory, 1 one row per candidate in LDS updated in
- *          place, 2 two rows in LDS; [4] waves per candidate, [5] candidates per workgroup,
+ *          place, 2 two rows in LDS, 3 / 4 as 1 / 0 in a workgroup of twice the waves (D record:
+ *          rows too long for launch 1); [4] waves per candidate, [5] candidates per workgroup,
  *          [6] 1 if rows are updated in place; and what that choice was made from: [7] bytes of
  *          LDS for the windows of launch 0, [8] waves per workgroup, [9] most 64-bucket chunks a
  *          wave keeps in registers, [10] / [11] dynamic LDS bytes of launches 1 / 2 (0: not
  *          enqueued), [12] floats of +inf apron left of a row, [13] 1 if launch 1 ran with
  *          twice the waves of [8], the second half dividing each layer's levels with the first
- *          (D record, S <= 64, no more candidates than compute units).  Per-layer arrays follow the
+ *          (D record, S <= 64, no more candidates than compute units), [14] waves of launch 3
+ *          (0: not enqueued), [15] most chunks one of them keeps in registers, [16] its dynamic
+ *          LDS bytes, [17] waves of the global-row launch.  Per-layer arrays follow the
  *          out[6] header words: m_l at [out[6] + l], the number of computed 64-bucket chunks of
  *          layer l at [out[6] + L + l], the largest usable shift of layer l at
  *          [out[6] + (2 + out[7]) L + l]
