@@ -185,6 +185,7 @@ EDGE_SHAPES = [
                           # workgroups per unit with half-size windows)
     (2, 300, 3, 500),                                # more layers than prepare threads
     (2, 5, 64, 300), (2, 5, 65, 300), (3, 4, 129, 900),       # level-block boundaries
+    (2, 3, 70, 20480), (1, 3, 70, 40000),            # ... with long rows (LDS, global memory)
     (37, 4, 5, 200), (19, 3, 6, 1500),               # few candidates: one team per workgroup
     # more candidates than the chip holds at once: several teams per workgroup, the last
     # workgroup partly filled
