@@ -30,10 +30,16 @@
 //     that each wave owns as many chunks as its registers hold whatever the reduced row length
 //     is; when every wave holds all its chunks of the row in registers the row is updated in
 //     place (one row per candidate), otherwise two rows alternate;
-//   * two workgroups share a compute unit, and in a launch of one or two rounds of workgroups
-//     they take turns at the instruction priority, so that neither runs on the other's leftovers
-//     and then alone.
-// When two reduced rows do not fit in LDS the same kernel runs with the rows in global memory.
+//   * two workgroups of eight waves share a compute unit, and in a launch of one or two rounds
+//     of workgroups they take turns at the instruction priority, so that neither runs on the
+//     other's leftovers and then alone;
+//   * a compute unit wants about sixteen waves of this loop, each with a long group.  Where the
+//     usual shape does not give that, a D-record workgroup has sixteen waves: with no more
+//     candidates than compute units the second eight divide each layer's ENTRIES with the first
+//     eight on the same chunks; a row too long for eight waves' registers is updated in place by
+//     sixteen waves with up to the whole LDS of the unit.
+// A row that is longer still lives in global memory (two alternating rows per candidate) and is
+// computed tile by tile, the part of the previous row a tile reads being staged in LDS first.
 #include <hip/hip_runtime.h>
 
 #include <stdint.h>
