@@ -170,6 +170,33 @@ def test_config_bit_exact(dp, name, compact, reference):
         check_tables(dp, tau, err[k], B, ws, k, cfg.K)
 
 
+@pytest.mark.parametrize("name", ["stress_x38_k256", "stress_x30_k256", "stress_x25_k256",
+                                  "rn50_b100k_k1024", "rn50_s128_k1024"])
+def test_long_row_workloads_on_sampled_candidates(dp, name):
+    """The workloads that take the other launches of the fill (one long row in LDS swept by
+    sixteen waves, rows in global memory, more than 64 levels), at the sizes their profiles are
+    taken on: the whole batch is solved, sixteen candidates spread over it are compared with the
+    oracle (one of them table by table), and the properties that need no oracle are checked on
+    all of them."""
+    cfg = workloads.CONFIGS[name]
+    print(f"[parity] workload {name}: K={cfg.K} L={cfg.L} S={cfg.S} B={cfg.B}", flush=True)
+    tau, err, B = workloads.generate(cfg)
+    p_gpu, c_gpu, ws = gpu_solve(dp, tau, err, B)
+    print(f"[parity] {name}: gpu done", flush=True)
+    pick = np.unique(np.linspace(0, cfg.K - 1, 16).astype(np.int64))
+    p_ref, c_ref = oracle.solve_ref(tau, np.ascontiguousarray(err[pick]), B, threads=CPU_THREADS)
+    assert_same(p_gpu[pick], c_gpu[pick], p_ref, c_ref, name)
+    t = np.take_along_axis(np.broadcast_to(tau, err.shape), p_gpu[:, :, None].astype(np.int64),
+                           axis=2)[:, :, 0].sum(axis=1)
+    assert (t <= B).all()
+    e = np.take_along_axis(err, p_gpu[:, :, None].astype(np.int64), axis=2)[:, :, 0]
+    acc = e[:, 0].copy()
+    for l in range(1, cfg.L):
+        acc = (acc + e[:, l]).astype(np.float32)
+    assert (acc.view(np.uint32) == c_gpu.view(np.uint32)).all()
+    check_tables(dp, tau, err[cfg.K - 1], B, ws, cfg.K - 1, cfg.K)
+
+
 # --------------------------------------------------------------------------- shapes and edges
 EDGE_SHAPES = [
     # K, L, S, B  (B + 1 deliberately not a multiple of 64 in most; several chunks per wave)
